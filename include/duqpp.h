@@ -1,0 +1,145 @@
+/*
+ * duqpp.h -- C ABI of the DuQuant++ online inference hot path for AMD MI355X (gfx950).
+ *
+ * The path is the reformulated linear layer of the paper's Eq. 5 (Sec. 4.2):
+ *
+ *     Y = Q(X . R^) . Q(R^T . W)
+ *
+ * where R^ = BlockDiag(R_1 .. R_G) is orthogonal with 32x32 blocks aligned to the MXFP4
+ * groups (Eq. 4, B = 32) and Q is MXFP4 quantisation (Sec. 3.2, Eq. 2): every 32
+ * consecutive values along the reduction axis K share one E8M0 power-of-two scale
+ * 2^(floor(log2 amax) - 2) and are stored as 4-bit E2M1 codes (round to nearest, ties to
+ * even, saturating at +-6).  The smoothing diagonal of Eq. 3 is not applied on this path.
+ *
+ * Conventions (all entry points)
+ *   - Every pointer is a DEVICE pointer unless its comment says "host".  The caller owns
+ *     every buffer; the library allocates nothing and keeps no device state.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work and return; they never synchronise.
+ *   - Layouts are row-major with K contiguous.  G = K / 32.
+ *       X       bf16  [T, K]      row stride ldx (elements)
+ *       W       bf16  [N, K]      row n = output channel n (a Linear's weight), stride ldw
+ *       R       fp32  [n_rblocks, 32, 32], R[j][r][c]: r = input channel of block j,
+ *               c = output channel, so y[32j + c] = sum_r x[32j + r] * R[j][r][c]
+ *               (row-vector form X . R^ of Eq. 5).  n_rblocks == G, or 1 when every
+ *               group shares one block (the shared-matrix variant of Sec. 4.2).
+ *       codes   uint8 [rows, K/2] element 2i in the LOW nibble of byte i, 2i+1 in the high
+ *               nibble; code = sign<<3 | magnitude index into {0, .5, 1, 1.5, 2, 3, 4, 6}
+ *       scales  uint8 [rows, G]   E8M0: value 2^(byte - 127); 0xFF is never produced
+ *       Y       fp32 or bf16 [T, N], row stride ldy (elements)
+ *   - Requirements checked on the host before any launch: pointers non-null, T/N >= 1,
+ *     K >= 32 and K % 32 == 0, n_rblocks in {1, K/32}, ld >= the row length, X/W bases and
+ *     row strides 16-byte aligned, codes bases 16-byte aligned, Y base aligned to its element.
+ *   - Inputs must be finite; NaN/Inf are outside the contract.
+ *   - Return value: DUQPP_OK or a negative duqpp_status; nothing throws or aborts.
+ *   - Results are deterministic: the same inputs give bit-identical outputs on every call.
+ */
+#ifndef DUQPP_H
+#define DUQPP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DUQPP_OK = 0,
+    DUQPP_ERR_NULL = -1,      /* a required pointer is null */
+    DUQPP_ERR_SHAPE = -2,     /* bad T/N/K/ld/n_rblocks */
+    DUQPP_ERR_ALIGN = -3,     /* base pointer or stride not aligned as required */
+    DUQPP_ERR_DTYPE = -4,     /* out_dtype is not a duqpp_dtype */
+    DUQPP_ERR_WORKSPACE = -5, /* workspace missing or smaller than duqpp_gemm_workspace_bytes */
+    DUQPP_ERR_ARCH = -6,      /* the current device is not gfx950 */
+    DUQPP_ERR_HIP = -7        /* a HIP runtime call or launch failed */
+} duqpp_status;
+
+typedef enum { DUQPP_F32 = 0, DUQPP_BF16 = 1 } duqpp_dtype;
+
+/*
+ * Offline weight transform of Eq. 5: W^ = R^T . W, then Eq. 2 along K.  With W stored
+ * [N, K], each row is rotated exactly like a token (W^T . R^).
+ *   w_bf16   in   [N, K] bf16, stride ldw
+ *   R        in   [n_rblocks, 32, 32] fp32
+ *   w_codes  out  [N, K/2];  w_scales out [N, K/32]
+ */
+int duqpp_quantize_weights(const void* w_bf16, int64_t N, int64_t K, int64_t ldw,
+                           const float* R, int64_t n_rblocks,
+                           uint8_t* w_codes, uint8_t* w_scales, void* stream);
+
+/*
+ * Online activation transform of Eq. 5 (Remark 2: the only online extra is X -> X . R^):
+ * rotate every 32-channel block of every token by its block of R^ (Eq. 4), then quantise
+ * to MXFP4 (Eq. 2).
+ *   x_bf16     in   [T, K] bf16, stride ldx
+ *   x_codes    out  [T, K/2];  x_scales out [T, K/32]
+ *   y_rot_dbg  out  nullable; when given, [T, K] fp32 (stride K) receives the rotated values
+ *                   the quantiser saw (used by parity tests; costs extra HBM traffic)
+ */
+int duqpp_rotate_quantize(const void* x_bf16, int64_t T, int64_t K, int64_t ldx,
+                          const float* R, int64_t n_rblocks,
+                          uint8_t* x_codes, uint8_t* x_scales,
+                          float* y_rot_dbg, void* stream);
+
+/*
+ * W4A4 MXFP4 product of Eq. 5: Y[t, n] = sum_k val_a[t, k] * val_b[n, k], where val is the
+ * value a code and its group scale stand for.  Products of E2M1 values are exact; sums are
+ * accumulated in fp32 on the block-scaled matrix cores.
+ *   a_codes/a_scales  in   [T, K/2], [T, K/32]   (from duqpp_rotate_quantize)
+ *   b_codes/b_scales  in   [N, K/2], [N, K/32]   (from duqpp_quantize_weights)
+ *   y                 out  [T, N] of out_dtype (duqpp_dtype), stride ldy; bf16 output is the
+ *                          round-to-nearest-even of the fp32 result
+ *   workspace         scratch of at least duqpp_gemm_workspace_bytes(T, N, K, 0) bytes,
+ *                     256-byte aligned; may be null when that size is 0
+ */
+int duqpp_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
+                     const uint8_t* b_codes, const uint8_t* b_scales,
+                     int64_t T, int64_t N, int64_t K,
+                     void* y, int out_dtype, int64_t ldy,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Fused form of the online path: Y = Q(X . R^) . Q(W^) in one call, producing exactly the
+ * codes duqpp_rotate_quantize would and the product duqpp_mxfp4_gemm would.
+ *   workspace  at least duqpp_gemm_workspace_bytes(T, N, K, 1) bytes, 256-byte aligned
+ */
+int duqpp_rotq_gemm(const void* x_bf16, int64_t ldx, const float* R, int64_t n_rblocks,
+                    const uint8_t* b_codes, const uint8_t* b_scales,
+                    int64_t T, int64_t N, int64_t K,
+                    void* y, int out_dtype, int64_t ldy,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * TEST ONLY: runs the quantiser stage of duqpp_rotate_quantize (group amax, E8M0 scale,
+ * E2M1 rounding, packing -- Eq. 2) on caller-supplied fp32 values, so that every fp32 bit
+ * pattern can be swept through the device code.
+ *   y  in  [rows, K] fp32, stride ldy (elements, multiple of 4)
+ */
+int duqpp_quantize_f32_dbg(const float* y, int64_t rows, int64_t K, int64_t ldy,
+                           uint8_t* codes, uint8_t* scales, void* stream);
+
+/* Host, pure: scratch bytes duqpp_mxfp4_gemm (fused = 0) or duqpp_rotq_gemm (fused = 1) needs. */
+size_t duqpp_gemm_workspace_bytes(int64_t T, int64_t N, int64_t K, int fused);
+
+/*
+ * Host-only argument checks, exactly the ones the entry points run before launching.
+ * They never touch the device, so they can be called without a GPU.
+ */
+int duqpp_validate_rotate_quantize(const void* x_bf16, int64_t T, int64_t K, int64_t ldx,
+                                   const float* R, int64_t n_rblocks,
+                                   const uint8_t* codes, const uint8_t* scales);
+int duqpp_validate_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
+                              const uint8_t* b_codes, const uint8_t* b_scales,
+                              int64_t T, int64_t N, int64_t K,
+                              const void* y, int out_dtype, int64_t ldy,
+                              const void* workspace, size_t workspace_bytes, int fused);
+
+/* Static strings. */
+const char* duqpp_status_string(int status);
+const char* duqpp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DUQPP_H */

@@ -1,0 +1,19 @@
+"""DuQuant++ online hot path for AMD MI355X: thin Python binding over libduqpp's C ABI.
+
+Every step (block rotation, MXFP4 quantisation, W4A4 GEMM) runs in the library's HIP
+kernels; this module only marshals torch device tensors into raw pointers and sizes.
+There is no CPU or PyTorch fallback: importing without the built library raises.
+"""
+from .binding import (  # noqa: F401
+    DuqppError,
+    gemm_workspace_bytes,
+    lib,
+    library_path,
+    mxfp4_gemm,
+    quantize_f32_dbg,
+    quantize_weights,
+    rotate_quantize,
+    rotq_gemm,
+    status_string,
+    version,
+)

@@ -1,0 +1,185 @@
+"""ctypes binding with the same names as the C ABI (include/duqpp.h).  Argument marshalling only."""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libduqpp.so"
+
+F32, BF16 = 0, 1
+
+
+class DuqppError(RuntimeError):
+    def __init__(self, status, what):
+        super().__init__(f"{what}: {status_string(status)} ({status})")
+        self.status = status
+
+
+def library_path():
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def _load():
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(
+            f"{path} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'); "
+            "there is no fallback path")
+    L = ctypes.CDLL(path)
+    vp, i64, u8p, fp, sz, ci = (ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                                ctypes.c_size_t, ctypes.c_int)
+    L.duqpp_quantize_weights.argtypes = [vp, i64, i64, i64, fp, i64, u8p, u8p, vp]
+    L.duqpp_rotate_quantize.argtypes = [vp, i64, i64, i64, fp, i64, u8p, u8p, fp, vp]
+    L.duqpp_mxfp4_gemm.argtypes = [u8p, u8p, u8p, u8p, i64, i64, i64, vp, ci, i64, vp, sz, vp]
+    L.duqpp_rotq_gemm.argtypes = [vp, i64, fp, i64, u8p, u8p, i64, i64, i64, vp, ci, i64, vp, sz, vp]
+    L.duqpp_quantize_f32_dbg.argtypes = [fp, i64, i64, i64, u8p, u8p, vp]
+    L.duqpp_gemm_workspace_bytes.argtypes = [i64, i64, i64, ci]
+    L.duqpp_gemm_workspace_bytes.restype = sz
+    L.duqpp_validate_rotate_quantize.argtypes = [vp, i64, i64, i64, fp, i64, u8p, u8p]
+    L.duqpp_validate_mxfp4_gemm.argtypes = [u8p, u8p, u8p, u8p, i64, i64, i64, vp, ci, i64, vp, sz, ci]
+    for name in ("duqpp_quantize_weights", "duqpp_rotate_quantize", "duqpp_mxfp4_gemm", "duqpp_rotq_gemm",
+                 "duqpp_quantize_f32_dbg", "duqpp_validate_rotate_quantize", "duqpp_validate_mxfp4_gemm"):
+        getattr(L, name).restype = ci
+    L.duqpp_status_string.argtypes = [ci]
+    L.duqpp_status_string.restype = ctypes.c_char_p
+    L.duqpp_version.restype = ctypes.c_char_p
+    return L
+
+
+lib = _load()
+
+
+def status_string(status):
+    return lib.duqpp_status_string(int(status)).decode()
+
+
+def version():
+    return lib.duqpp_version().decode()
+
+
+def _check(status, what):
+    if status != 0:
+        raise DuqppError(status, what)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, what):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype):
+        raise TypeError(f"{what} must be a cuda tensor of {dtype}")
+    return t
+
+
+def _n_rblocks(R):
+    if R.dim() != 3 or tuple(R.shape[1:]) != (32, 32) or not R.is_contiguous():
+        raise ValueError("R must be a contiguous [n_rblocks, 32, 32] fp32 tensor")
+    return R.shape[0]
+
+
+def gemm_workspace_bytes(T, N, K, fused=False):
+    return int(lib.duqpp_gemm_workspace_bytes(T, N, K, int(bool(fused))))
+
+
+def _workspace(nbytes, device):
+    if nbytes == 0:
+        return None, 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)   # torch device allocations are >= 256-byte aligned
+    return ws, nbytes
+
+
+def _rows_op(fn_name, x, R, want_rot):
+    _dev(x, torch.bfloat16, "x")
+    _dev(R, torch.float32, "R")
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be [rows, K] with unit stride along K")
+    rows, K = x.shape
+    codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=x.device)
+    scales = torch.empty((rows, K // 32), dtype=torch.uint8, device=x.device)
+    nb = _n_rblocks(R)
+    if fn_name == "duqpp_rotate_quantize":
+        yrot = torch.empty((rows, K), dtype=torch.float32, device=x.device) if want_rot else None
+        st = lib.duqpp_rotate_quantize(x.data_ptr(), rows, K, x.stride(0), R.data_ptr(), nb, codes.data_ptr(),
+                                       scales.data_ptr(), yrot.data_ptr() if want_rot else None, _stream())
+        _check(st, fn_name)
+        return (codes, scales, yrot) if want_rot else (codes, scales)
+    st = lib.duqpp_quantize_weights(x.data_ptr(), rows, K, x.stride(0), R.data_ptr(), nb, codes.data_ptr(),
+                                    scales.data_ptr(), _stream())
+    _check(st, fn_name)
+    return codes, scales
+
+
+def rotate_quantize(x, R, return_rotated=False):
+    """x bf16 [T, K], R fp32 [K/32 or 1, 32, 32] -> (codes u8 [T, K/2], scales u8 [T, K/32][, y_rot fp32 [T, K]])."""
+    return _rows_op("duqpp_rotate_quantize", x, R, return_rotated)
+
+
+def quantize_weights(w, R):
+    """w bf16 [N, K] -> (codes u8 [N, K/2], scales u8 [N, K/32]) of R^T W."""
+    return _rows_op("duqpp_quantize_weights", w, R, False)
+
+
+def _out(T, N, out_dtype, device, out):
+    tdt = torch.float32 if out_dtype == F32 else torch.bfloat16
+    if out is None:
+        out = torch.empty((T, N), dtype=tdt, device=device)
+    elif out.dtype != tdt or tuple(out.shape) != (T, N) or out.stride(1) != 1:
+        raise ValueError("bad output tensor")
+    return out
+
+
+def mxfp4_gemm(a_codes, a_scales, b_codes, b_scales, out_dtype=F32, out=None, workspace=None):
+    for t, n in ((a_codes, "a_codes"), (a_scales, "a_scales"), (b_codes, "b_codes"), (b_scales, "b_scales")):
+        _dev(t, torch.uint8, n)
+        if not t.is_contiguous():
+            raise ValueError(f"{n} must be contiguous")
+    T, K = a_codes.shape[0], a_codes.shape[1] * 2
+    N = b_codes.shape[0]
+    if b_codes.shape[1] * 2 != K or tuple(a_scales.shape) != (T, K // 32) or tuple(b_scales.shape) != (N, K // 32):
+        raise ValueError("operand shapes disagree")
+    y = _out(T, N, out_dtype, a_codes.device, out)
+    if workspace is None:
+        workspace, nbytes = _workspace(gemm_workspace_bytes(T, N, K, False), a_codes.device)
+    else:
+        nbytes = workspace.numel()
+    st = lib.duqpp_mxfp4_gemm(a_codes.data_ptr(), a_scales.data_ptr(), b_codes.data_ptr(), b_scales.data_ptr(),
+                              T, N, K, y.data_ptr(), out_dtype, y.stride(0),
+                              workspace.data_ptr() if workspace is not None else None, nbytes, _stream())
+    _check(st, "duqpp_mxfp4_gemm")
+    return y
+
+
+def rotq_gemm(x, R, b_codes, b_scales, out_dtype=F32, out=None, workspace=None):
+    _dev(x, torch.bfloat16, "x")
+    _dev(R, torch.float32, "R")
+    _dev(b_codes, torch.uint8, "b_codes")
+    _dev(b_scales, torch.uint8, "b_scales")
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be [T, K] with unit stride along K")
+    T, K = x.shape
+    N = b_codes.shape[0]
+    if b_codes.shape[1] * 2 != K or tuple(b_scales.shape) != (N, K // 32):
+        raise ValueError("operand shapes disagree")
+    y = _out(T, N, out_dtype, x.device, out)
+    if workspace is None:
+        workspace, nbytes = _workspace(gemm_workspace_bytes(T, N, K, True), x.device)
+    else:
+        nbytes = workspace.numel()
+    st = lib.duqpp_rotq_gemm(x.data_ptr(), x.stride(0), R.data_ptr(), _n_rblocks(R), b_codes.data_ptr(),
+                             b_scales.data_ptr(), T, N, K, y.data_ptr(), out_dtype, y.stride(0),
+                             workspace.data_ptr() if workspace is not None else None, nbytes, _stream())
+    _check(st, "duqpp_rotq_gemm")
+    return y
+
+
+def quantize_f32_dbg(y):
+    """Test only: the device quantiser stage on fp32 [rows, K]."""
+    _dev(y, torch.float32, "y")
+    rows, K = y.shape
+    codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=y.device)
+    scales = torch.empty((rows, K // 32), dtype=torch.uint8, device=y.device)
+    st = lib.duqpp_quantize_f32_dbg(y.data_ptr(), rows, K, y.stride(0), codes.data_ptr(), scales.data_ptr(), _stream())
+    _check(st, "duqpp_quantize_f32_dbg")
+    return codes, scales

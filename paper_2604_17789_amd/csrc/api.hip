@@ -1,0 +1,180 @@
+// C ABI of libduqpp: argument validation on the host, then kernel launches on the caller's stream.
+#include <atomic>
+#include <cstring>
+
+#include "duqpp_internal.h"
+
+using namespace duqpp;
+
+namespace {
+
+inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// One gfx950 check per device, cached.  0 = unknown, 1 = ok, 2 = wrong architecture.
+std::atomic<int> g_arch_state[64];
+
+int check_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return DUQPP_ERR_HIP; }
+    if (dev < 0 || dev >= 64) return DUQPP_ERR_HIP;
+    int st = g_arch_state[dev].load(std::memory_order_relaxed);
+    if (st == 0) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return DUQPP_ERR_HIP; }
+        st = (std::strncmp(prop.gcnArchName, "gfx950", 6) == 0) ? 1 : 2;
+        g_arch_state[dev].store(st, std::memory_order_relaxed);
+    }
+    return st == 1 ? DUQPP_OK : DUQPP_ERR_ARCH;
+}
+
+int validate_rows_K(int64_t rows, int64_t K, int64_t ld, int64_t n_rblocks) {
+    if (rows < 1 || rows > (int64_t)1 << 30) return DUQPP_ERR_SHAPE;
+    if (K < 32 || (K % 32) != 0 || K > (int64_t)1 << 30) return DUQPP_ERR_SHAPE;
+    if (ld < K) return DUQPP_ERR_SHAPE;
+    if (n_rblocks != 1 && n_rblocks != K / 32) return DUQPP_ERR_SHAPE;
+    return DUQPP_OK;
+}
+
+int rotate_quantize_impl(const void* x, int64_t rows, int64_t K, int64_t ldx, const float* R, int64_t n_rblocks,
+                         uint8_t* codes, uint8_t* scales, float* ydbg, void* stream) {
+    int st = duqpp_validate_rotate_quantize(x, rows, K, ldx, R, n_rblocks, codes, scales);
+    if (st != DUQPP_OK) return st;
+    if (ydbg && !aligned_to(ydbg, 16)) return DUQPP_ERR_ALIGN;
+    st = check_device();
+    if (st != DUQPP_OK) return st;
+    RotqParams p{};
+    p.x = static_cast<const uint16_t*>(x);
+    p.ldx = ldx;
+    p.rows = (int)rows;
+    p.G = (int)(K / 32);
+    p.R = R;
+    p.r_stride = (n_rblocks == 1) ? 0 : 32 * 32;
+    p.codes = codes;
+    p.scales = scales;
+    p.ydbg = ydbg;
+    plan_rotq(p);
+    return launch_rotq(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
+}
+
+// layout of the fused call's scratch: A codes, then A scales (256-byte aligned), then the GEMM's own
+size_t fused_codes_bytes(int64_t T, int64_t K) { return ((size_t)T * (size_t)(K / 2) + 255) & ~(size_t)255; }
+size_t fused_scales_bytes(int64_t T, int64_t K) { return ((size_t)T * (size_t)(K / 32) + 255) & ~(size_t)255; }
+
+}  // namespace
+
+extern "C" {
+
+int duqpp_validate_rotate_quantize(const void* x, int64_t T, int64_t K, int64_t ldx, const float* R,
+                                   int64_t n_rblocks, const uint8_t* codes, const uint8_t* scales) {
+    if (!x || !R || !codes || !scales) return DUQPP_ERR_NULL;
+    int st = validate_rows_K(T, K, ldx, n_rblocks);
+    if (st != DUQPP_OK) return st;
+    if (!aligned_to(x, 16) || (ldx % 8) != 0) return DUQPP_ERR_ALIGN;
+    if (!aligned_to(R, 4) || !aligned_to(codes, 16)) return DUQPP_ERR_ALIGN;
+    return DUQPP_OK;
+}
+
+int duqpp_validate_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
+                              const uint8_t* b_scales, int64_t T, int64_t N, int64_t K, const void* y,
+                              int out_dtype, int64_t ldy, const void* workspace, size_t workspace_bytes,
+                              int fused) {
+    if (!a_codes || !b_codes || !b_scales || !y) return DUQPP_ERR_NULL;
+    if (!fused && !a_scales) return DUQPP_ERR_NULL;
+    if (T < 1 || N < 1 || T > (int64_t)1 << 30 || N > (int64_t)1 << 30) return DUQPP_ERR_SHAPE;
+    if (K < 32 || (K % 32) != 0 || K > (int64_t)1 << 30) return DUQPP_ERR_SHAPE;
+    if (ldy < N) return DUQPP_ERR_SHAPE;
+    if (out_dtype != DUQPP_F32 && out_dtype != DUQPP_BF16) return DUQPP_ERR_DTYPE;
+    if (!aligned_to(b_codes, 16)) return DUQPP_ERR_ALIGN;
+    if (!fused && !aligned_to(a_codes, 16)) return DUQPP_ERR_ALIGN;
+    if (!aligned_to(y, out_dtype == DUQPP_F32 ? 4 : 2)) return DUQPP_ERR_ALIGN;
+    size_t need = duqpp_gemm_workspace_bytes(T, N, K, fused);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return DUQPP_ERR_WORKSPACE;
+        if (!aligned_to(workspace, 256)) return DUQPP_ERR_ALIGN;
+    }
+    return DUQPP_OK;
+}
+
+size_t duqpp_gemm_workspace_bytes(int64_t T, int64_t N, int64_t K, int fused) {
+    if (T < 1 || N < 1 || K < 32) return 0;
+    size_t w = gemm_workspace_bytes(T, N, K);
+    if (fused) w += fused_codes_bytes(T, K) + fused_scales_bytes(T, K);
+    return w;
+}
+
+int duqpp_rotate_quantize(const void* x_bf16, int64_t T, int64_t K, int64_t ldx, const float* R,
+                          int64_t n_rblocks, uint8_t* x_codes, uint8_t* x_scales, float* y_rot_dbg,
+                          void* stream) {
+    return rotate_quantize_impl(x_bf16, T, K, ldx, R, n_rblocks, x_codes, x_scales, y_rot_dbg, stream);
+}
+
+int duqpp_quantize_weights(const void* w_bf16, int64_t N, int64_t K, int64_t ldw, const float* R,
+                           int64_t n_rblocks, uint8_t* w_codes, uint8_t* w_scales, void* stream) {
+    return rotate_quantize_impl(w_bf16, N, K, ldw, R, n_rblocks, w_codes, w_scales, nullptr, stream);
+}
+
+int duqpp_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
+                     const uint8_t* b_scales, int64_t T, int64_t N, int64_t K, void* y, int out_dtype,
+                     int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+    int st = duqpp_validate_mxfp4_gemm(a_codes, a_scales, b_codes, b_scales, T, N, K, y, out_dtype, ldy,
+                                       workspace, workspace_bytes, 0);
+    if (st != DUQPP_OK) return st;
+    st = check_device();
+    if (st != DUQPP_OK) return st;
+    GemmParams p{};
+    p.a_codes = a_codes; p.a_scales = a_scales; p.b_codes = b_codes; p.b_scales = b_scales;
+    p.T = (int)T; p.N = (int)N; p.G = (int)(K / 32);
+    p.y = y; p.ldy = ldy; p.out_bf16 = (out_dtype == DUQPP_BF16);
+    p.workspace = workspace; p.workspace_bytes = workspace_bytes;
+    return launch_gemm(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
+}
+
+int duqpp_rotq_gemm(const void* x_bf16, int64_t ldx, const float* R, int64_t n_rblocks,
+                    const uint8_t* b_codes, const uint8_t* b_scales, int64_t T, int64_t N, int64_t K,
+                    void* y, int out_dtype, int64_t ldy, void* workspace, size_t workspace_bytes,
+                    void* stream) {
+    if (!x_bf16 || !R) return DUQPP_ERR_NULL;
+    // the A-side codes live in the workspace: validate the GEMM part with it standing in for them
+    int st = duqpp_validate_mxfp4_gemm(static_cast<const uint8_t*>(workspace), nullptr, b_codes, b_scales, T, N, K,
+                                       y, out_dtype, ldy, workspace, workspace_bytes, 1);
+    if (st == DUQPP_ERR_NULL && !workspace && b_codes && b_scales && y) st = DUQPP_ERR_WORKSPACE;
+    if (st != DUQPP_OK) return st;
+    uint8_t* a_codes = static_cast<uint8_t*>(workspace);
+    uint8_t* a_scales = a_codes + fused_codes_bytes(T, K);
+    uint8_t* rest = a_scales + fused_scales_bytes(T, K);
+    size_t rest_bytes = workspace_bytes - fused_codes_bytes(T, K) - fused_scales_bytes(T, K);
+    st = rotate_quantize_impl(x_bf16, T, K, ldx, R, n_rblocks, a_codes, a_scales, nullptr, stream);
+    if (st != DUQPP_OK) return st;
+    return duqpp_mxfp4_gemm(a_codes, a_scales, b_codes, b_scales, T, N, K, y, out_dtype, ldy,
+                            rest_bytes ? rest : nullptr, rest_bytes, stream);
+}
+
+int duqpp_quantize_f32_dbg(const float* y, int64_t rows, int64_t K, int64_t ldy, uint8_t* codes,
+                           uint8_t* scales, void* stream) {
+    if (!y || !codes || !scales) return DUQPP_ERR_NULL;
+    int st = validate_rows_K(rows, K, ldy, 1);
+    if (st != DUQPP_OK) return st;
+    if (!aligned_to(y, 16) || (ldy % 4) != 0 || !aligned_to(codes, 16)) return DUQPP_ERR_ALIGN;
+    st = check_device();
+    if (st != DUQPP_OK) return st;
+    QuantDbgParams p{y, ldy, (int)rows, (int)(K / 32), codes, scales};
+    return launch_quant_dbg(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
+}
+
+const char* duqpp_status_string(int status) {
+    switch (status) {
+        case DUQPP_OK: return "ok";
+        case DUQPP_ERR_NULL: return "null pointer";
+        case DUQPP_ERR_SHAPE: return "bad shape";
+        case DUQPP_ERR_ALIGN: return "misaligned pointer or stride";
+        case DUQPP_ERR_DTYPE: return "bad output dtype";
+        case DUQPP_ERR_WORKSPACE: return "workspace missing or too small";
+        case DUQPP_ERR_ARCH: return "device is not gfx950";
+        case DUQPP_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+const char* duqpp_version(void) { return "duqpp 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -1,0 +1,104 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/duqpp.h declares, and
+its host-side argument validation returns the documented codes without touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "duqpp.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2604_17789_amd as duqpp
+    return duqpp.lib
+
+
+def _declared_symbols():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(duqpp_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_header_declares_the_four_entry_points():
+    names = _declared_symbols()
+    for n in ("duqpp_quantize_weights", "duqpp_rotate_quantize", "duqpp_mxfp4_gemm", "duqpp_rotq_gemm"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in _declared_symbols():
+        assert hasattr(lib, name), name
+
+
+def test_status_strings_and_version(lib):
+    assert lib.duqpp_status_string(0) == b"ok"
+    seen = {lib.duqpp_status_string(-i) for i in range(0, 8)}
+    assert len(seen) == 8
+    assert lib.duqpp_status_string(-99) == b"unknown status"
+    assert b"gfx950" in lib.duqpp_version()
+
+
+OK, NULL, SHAPE, ALIGN, DTYPE, WORKSPACE = 0, -1, -2, -3, -4, -5
+P = 0x10000   # a fake, well-aligned, never dereferenced device address
+
+
+def test_validate_rotate_quantize(lib):
+    v = lib.duqpp_validate_rotate_quantize
+    assert v(P, 4, 64, 64, P, 2, P, P) == OK
+    assert v(P, 4, 64, 64, P, 1, P, P) == OK            # shared block
+    assert v(None, 4, 64, 64, P, 2, P, P) == NULL
+    assert v(P, 4, 64, 64, None, 2, P, P) == NULL
+    assert v(P, 4, 64, 64, P, 2, None, P) == NULL
+    assert v(P, 4, 64, 64, P, 2, P, None) == NULL
+    assert v(P, 0, 64, 64, P, 2, P, P) == SHAPE
+    assert v(P, 4, 48, 64, P, 1, P, P) == SHAPE         # K % 32
+    assert v(P, 4, 0, 64, P, 1, P, P) == SHAPE
+    assert v(P, 4, 64, 32, P, 2, P, P) == SHAPE         # ld < K
+    assert v(P, 4, 64, 64, P, 3, P, P) == SHAPE         # n_rblocks not in {1, K/32}
+    assert v(P + 2, 4, 64, 64, P, 2, P, P) == ALIGN
+    assert v(P, 4, 64, 68, P, 2, P, P) == ALIGN         # row stride not 16-byte aligned
+    assert v(P, 4, 64, 64, P, 2, P + 8, P) == ALIGN
+
+
+def test_validate_gemm(lib):
+    v = lib.duqpp_validate_mxfp4_gemm
+    assert v(P, P, P, P, 8, 16, 64, P, 0, 16, None, 0, 0) == OK
+    assert v(P, P, P, P, 8, 16, 64, P, 1, 16, None, 0, 0) == OK
+    assert v(None, P, P, P, 8, 16, 64, P, 0, 16, None, 0, 0) == NULL
+    assert v(P, None, P, P, 8, 16, 64, P, 0, 16, None, 0, 0) == NULL
+    assert v(P, P, P, P, 8, 16, 64, None, 0, 16, None, 0, 0) == NULL
+    assert v(P, P, P, P, 0, 16, 64, P, 0, 16, None, 0, 0) == SHAPE
+    assert v(P, P, P, P, 8, 16, 40, P, 0, 16, None, 0, 0) == SHAPE
+    assert v(P, P, P, P, 8, 16, 64, P, 0, 8, None, 0, 0) == SHAPE     # ldy < N
+    assert v(P, P, P, P, 8, 16, 64, P, 7, 16, None, 0, 0) == DTYPE
+    assert v(P, P, P + 4, P, 8, 16, 64, P, 0, 16, None, 0, 0) == ALIGN
+    assert v(P, P, P, P, 8, 16, 64, P + 2, 0, 16, None, 0, 0) == ALIGN
+    # the fused call needs room for the A-side codes and scales
+    need = lib.duqpp_gemm_workspace_bytes(8, 16, 64, 1)
+    assert need >= 8 * 32 + 8 * 2
+    assert v(P, None, P, P, 8, 16, 64, P, 0, 16, None, 0, 1) == WORKSPACE
+    assert v(P, None, P, P, 8, 16, 64, P, 0, 16, P, need - 1, 1) == WORKSPACE
+    assert v(P, None, P, P, 8, 16, 64, P, 0, 16, P + 64, need, 1) == ALIGN
+    assert v(P, None, P, P, 8, 16, 64, P, 0, 16, P, need, 1) == OK
+
+
+def test_entry_points_reject_bad_arguments_before_any_launch(lib):
+    # these return from the host-side checks, so they are safe without a device
+    assert lib.duqpp_rotate_quantize(None, 4, 64, 64, P, 2, P, P, None, None) == NULL
+    assert lib.duqpp_quantize_weights(P, 4, 50, 64, P, 2, P, P, None) == SHAPE
+    assert lib.duqpp_mxfp4_gemm(P, P, P, P, 8, 16, 64, P, 9, 16, None, 0, None) == DTYPE
+    assert lib.duqpp_rotq_gemm(P, 64, P, 2, P, P, 8, 16, 64, P, 0, 16, None, 0, None) == WORKSPACE
+    assert lib.duqpp_quantize_f32_dbg(None, 4, 64, 64, P, P, None) == NULL
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    import importlib
+
+    import paper_2604_17789_amd.binding as b
+    monkeypatch.setattr(b, "_HERE", str(tmp_path))
+    with pytest.raises(ImportError):
+        b._load()
+    importlib.reload(b)
