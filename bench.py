@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the DuQuant++ online hot path on one MI355X.
+
+A step is one pass of the whole path over one batch: rotate + MXFP4-quantise the activations
+(duqpp_rotate_quantize) and multiply them with the pre-rotated MXFP4 weights (duqpp_mxfp4_gemm).
+The workload is LLaMA-3-8B down_proj prefill (T=2048, K=14336, N=4096, bf16 output) with seeded
+synthetic inputs carrying injected outlier channels; the weights are prepared once, before timing.
+Batches rotate through several buffer sets so that inputs come from HBM rather than from the
+256 MB last-level cache.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "rotate+MXFP4-quant GB/s (%HBM peak); W4A4 MXFP4 GEMM TFLOPS (%MFMA peak)"
+HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
+FP4_PEAK_TFLOPS = 10100.0     # MI355X dense MXFP4 matrix peak, published (256 CU x 2.4 GHz x 16384 flop/clk/CU)
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None until measured.
+MEASURED_TRAFFIC = {"gemm": None, "rotq": None}
+
+
+def rotq_algorithmic_bytes(T, K):
+    # bf16 in (2 B) + code out (0.5 B) + scale out (1/32 B) per element, plus R once (4 KiB per block)
+    return T * K * (2.0 + 0.5 + 1.0 / 32.0) + 4096.0 * (K // 32)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="c2_8b_down_prefill")
+    ap.add_argument("--sets", type=int, default=8, help="distinct buffer sets the batches rotate through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the path shards by tokens or output channels "
+              "without exchange, see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2604_17789_amd as duqpp
+    import workloads as wl
+
+    assert torch.cuda.is_available(), "no GPU visible"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = wl.CONFIGS[args.config]
+    T, K, N = cfg["T"], cfg["K"], cfg["N"]
+    out_dtype = duqpp.binding.BF16 if cfg["out"] == "bf16" else duqpp.binding.F32
+    G = K // 32
+
+    def dev_bf16(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
+
+    # ---- inputs: resident in HBM before the timed region --------------------------------
+    nsets = max(1, args.sets)
+    sets = []
+    x0_bits = None
+    w0_bits = None
+    R0 = None
+    for s in range(nsets):
+        xb = wl.make_activations(f"bench-{args.config}-{s}", T, K, cfg["outliers"])
+        wb = wl.make_weights(f"bench-{args.config}-{s}", N, K, cfg["w_std"])
+        R = wl.make_rotation_blocks(f"bench-{args.config}-{s}", G)
+        if s == 0:
+            x0_bits, w0_bits, R0 = xb, wb, R
+        x, Rd = dev_bf16(xb), torch.from_numpy(R).to(dev)
+        w = dev_bf16(wb)
+        bc, bs = duqpp.quantize_weights(w, Rd)            # offline weight transform, not timed
+        del w
+        sets.append(dict(
+            x=x, R=Rd, bc=bc, bs=bs,
+            ac=torch.empty((T, K // 2), dtype=torch.uint8, device=dev),
+            asc=torch.empty((T, G), dtype=torch.uint8, device=dev),
+            y=torch.empty((T, N), dtype=torch.bfloat16 if cfg["out"] == "bf16" else torch.float32, device=dev)))
+    ws_bytes = duqpp.gemm_workspace_bytes(T, N, K, False)
+    ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=dev) if ws_bytes else None
+    torch.cuda.synchronize()
+
+    def rotq(s):
+        duqpp.rotate_quantize(s["x"], s["R"], out=(s["ac"], s["asc"]))
+
+    def gemm(s):
+        duqpp.mxfp4_gemm(s["ac"], s["asc"], s["bc"], s["bs"], out_dtype=out_dtype, out=s["y"], workspace=ws)
+
+    def step(i):
+        s = sets[i % nsets]
+        rotq(s)
+        gemm(s)
+
+    # ---- whole-step timing ---------------------------------------------------------------
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # ---- per-kernel timing with events on the launch stream -------------------------------
+    def time_kernel(fn):
+        for i in range(min(args.warmup, 10)):
+            fn(sets[i % nsets])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(args.steps):
+            fn(sets[i % nsets])
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / args.steps      # microseconds per launch
+
+    rotq_us = time_kernel(rotq)
+    gemm_us = time_kernel(gemm)
+
+    flops = 2.0 * T * N * K
+    rotq_bytes = rotq_algorithmic_bytes(T, K)
+    rotq_gbps = rotq_bytes / (rotq_us * 1e-6) / 1e9
+    gemm_tflops = flops / (gemm_us * 1e-6) / 1e12
+    value = flops / (ms_per_step * 1e-3) / 1e12
+
+    result = {
+        "metric": METRIC,
+        "value": round(value, 2),
+        "unit": "TFLOP/s (2*T*N*K per whole step: rotate+quantise, then GEMM)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "mxfp4 (E2M1 codes + E8M0 scales; fp32 rotation and accumulation)",
+        "data": "synthetic",
+        "config": {"workload": args.config, "T": T, "K": K, "N": N, "output": cfg["out"],
+                   "buffer_sets": nsets, "rotation_blocks": G},
+        "components": {
+            "rotate_quantize": {"us": round(rotq_us, 2), "GB/s": round(rotq_gbps, 1),
+                                "frac_hbm_peak": round(rotq_gbps / HBM_PEAK_GBPS, 4)},
+            "mxfp4_gemm": {"us": round(gemm_us, 2), "TFLOP/s": round(gemm_tflops, 1),
+                           "frac_mfma_peak": round(gemm_tflops / FP4_PEAK_TFLOPS, 4)},
+        },
+        "roofline": {"kernel": "mxfp4_gemm", "bound": "mfma", "achieved": round(gemm_tflops, 1),
+                     "peak": FP4_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(gemm_tflops / FP4_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC["gemm"]},
+        "roofline_rotate_quantize": {"kernel": "rotq", "bound": "hbm", "achieved": round(rotq_gbps, 1),
+                                     "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                     "frac": round(rotq_gbps / HBM_PEAK_GBPS, 4),
+                                     "traffic": MEASURED_TRAFFIC["rotq"]},
+    }
+
+    # ---- the CPU oracle on a bounded sample of the same workload ---------------------------
+    if not args.no_cpu_baseline:
+        import oracle
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            threads = os.cpu_count() or 1
+        Ts = min(T, 256)
+        s0 = sets[0]
+        bc_h, bs_h = s0["bc"].cpu().numpy(), s0["bs"].cpu().numpy()
+        c0 = time.perf_counter()
+        a_codes, a_scales, _ = oracle.pipeline.rotate_quantize(x0_bits[:Ts], R0)
+        y_ref = oracle.linear.mxfp4_gemm(a_codes, a_scales, bc_h, bs_h)
+        c1 = time.perf_counter()
+        result["cpu_baseline"] = {
+            "value": round(2.0 * Ts * N * K / (c1 - c0) / 1e12, 5), "unit": "TFLOP/s (whole step)",
+            "cores": int(threads), "kind": "oracle", "seconds": round(c1 - c0, 2),
+            "sample": f"first {Ts} of {T} tokens, full K and N (rotate+quantise then fp64 product)"}
+        # the sampled rows double as a live parity check of what was timed
+        rotq(s0)
+        gemm(s0)
+        torch.cuda.synchronize()
+        y_dev = s0["y"][:Ts].float().cpu().numpy()
+        a_dev = s0["ac"][:Ts].cpu().numpy()
+        result["parity"] = {
+            "codes_equal_fraction": float(np.mean(a_dev == a_codes)),
+            "gemm_rel_fro_vs_oracle_on_own_codes": float(
+                np.linalg.norm(y_dev - oracle.linear.mxfp4_gemm(a_dev, s0["asc"][:Ts].cpu().numpy(), bc_h, bs_h))
+                / np.linalg.norm(y_ref)),
+            "note": "bf16 output rounding (2^-9) bounds the second figure" if cfg["out"] == "bf16" else ""}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -90,14 +90,22 @@ def _workspace(nbytes, device):
     return ws, nbytes
 
 
-def _rows_op(fn_name, x, R, want_rot):
+def _rows_op(fn_name, x, R, want_rot, out=None):
     _dev(x, torch.bfloat16, "x")
     _dev(R, torch.float32, "R")
     if x.dim() != 2 or x.stride(1) != 1:
         raise ValueError("x must be [rows, K] with unit stride along K")
     rows, K = x.shape
-    codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=x.device)
-    scales = torch.empty((rows, K // 32), dtype=torch.uint8, device=x.device)
+    if out is None:
+        codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=x.device)
+        scales = torch.empty((rows, K // 32), dtype=torch.uint8, device=x.device)
+    else:
+        codes, scales = out
+        _dev(codes, torch.uint8, "codes")
+        _dev(scales, torch.uint8, "scales")
+        if (tuple(codes.shape) != (rows, K // 2) or tuple(scales.shape) != (rows, K // 32)
+                or not codes.is_contiguous() or not scales.is_contiguous()):
+            raise ValueError("bad output tensors")
     nb = _n_rblocks(R)
     if fn_name == "duqpp_rotate_quantize":
         yrot = torch.empty((rows, K), dtype=torch.float32, device=x.device) if want_rot else None
@@ -111,14 +119,15 @@ def _rows_op(fn_name, x, R, want_rot):
     return codes, scales
 
 
-def rotate_quantize(x, R, return_rotated=False):
-    """x bf16 [T, K], R fp32 [K/32 or 1, 32, 32] -> (codes u8 [T, K/2], scales u8 [T, K/32][, y_rot fp32 [T, K]])."""
-    return _rows_op("duqpp_rotate_quantize", x, R, return_rotated)
+def rotate_quantize(x, R, return_rotated=False, out=None):
+    """x bf16 [T, K], R fp32 [K/32 or 1, 32, 32] -> (codes u8 [T, K/2], scales u8 [T, K/32][, y_rot fp32 [T, K]]).
+    `out=(codes, scales)` reuses caller tensors."""
+    return _rows_op("duqpp_rotate_quantize", x, R, return_rotated, out)
 
 
-def quantize_weights(w, R):
+def quantize_weights(w, R, out=None):
     """w bf16 [N, K] -> (codes u8 [N, K/2], scales u8 [N, K/32]) of R^T W."""
-    return _rows_op("duqpp_quantize_weights", w, R, False)
+    return _rows_op("duqpp_quantize_weights", w, R, False, out)
 
 
 def _out(T, N, out_dtype, device, out):
