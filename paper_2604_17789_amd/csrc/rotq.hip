@@ -12,6 +12,8 @@
 // The quantiser uses the hardware E2M1 convert (v_cvt_scalef32_pk_fp4_f32), which rounds to
 // nearest even, saturates at 6, keeps the sign of zero and divides by the power of two held
 // in the exponent field of its scale operand (field 0 meaning 2^-127).
+#include <atomic>
+
 #include "duqpp_internal.h"
 
 namespace duqpp {
@@ -21,6 +23,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kRotqWaves = 8;              // wavefronts per workgroup
+constexpr int kRotqWGPerCU = 1;            // workgroups resident per CU (bounded by LDS)
 constexpr int kBlocksPerWave = 2;
 constexpr int kBlocksPerWG = kRotqWaves * kBlocksPerWave;
 
@@ -61,7 +64,7 @@ __device__ __forceinline__ void load_rot_operand(const float* __restrict__ Rb, i
 }
 
 // acc[i] of lane (t = lane & 31, h) is y[token t][channel 8 (i / 4) + 4 h + i % 4] of one block.
-__device__ __forceinline__ f32x16 rotate_tile(const RotOperand& op, const uint4 xv[2]) {
+__device__ __forceinline__ f32x16 rotate_tile(const RotOperand& op, const u32x4 xv[2]) {
     f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     bf16x8 b0 = __builtin_bit_cast(bf16x8, xv[0]);
     bf16x8 b1 = __builtin_bit_cast(bf16x8, xv[1]);
@@ -113,7 +116,99 @@ __device__ __forceinline__ void logical_workgroup(int& logical) {
     logical = xcd * per + (xcd < rem ? xcd : rem) + slot;
 }
 
-__global__ __launch_bounds__(kRotqWaves * 64) void rotq_kernel(RotqParams p) {
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* global_void_ptr;
+
+// LDS reads issued as asm: the compiler cannot tell which LDS-DMA transfer a read depends on
+// and would otherwise wait for ALL outstanding ones (vmcnt(0)) before every LDS read, which
+// would drain the prefetched tiles.  The waits that matter are placed by hand below.
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+    return (uint32_t)(uintptr_t)((__attribute__((address_space(3))) const void*)p);
+}
+__device__ __forceinline__ void lds_read4_b128(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3,
+                                               u32x4& r0, u32x4& r1, u32x4& r2, u32x4& r3) {
+    asm volatile(
+        "ds_read_b128 %0, %4\n\tds_read_b128 %1, %5\n\tds_read_b128 %2, %6\n\tds_read_b128 %3, %7\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(r0), "=&v"(r1), "=&v"(r2), "=&v"(r3)
+        : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+        : "memory");
+}
+__device__ __forceinline__ u32x4 lds_read_b128(uint32_t a) {
+    u32x4 r;
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(r) : "v"(a) : "memory");
+    return r;
+}
+// LDS writes of the output staging go the same way (the compiler would drain the DMA queue
+// before any LDS write it cannot prove disjoint from the DMA targets).
+__device__ __forceinline__ void lds_write_b64(uint32_t a, uint2 v) {
+    asm volatile("ds_write_b64 %0, %1" ::"v"(a), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_write_b8(uint32_t a, uint32_t v) {
+    asm volatile("ds_write_b8 %0, %1" ::"v"(a), "v"(v) : "memory");
+}
+// all LDS accesses of this wave have completed, then workgroup barrier
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Workgroup tile: 32 tokens x (WAVES * 2) blocks.  Per token row that is WAVES*128 bytes of
+// bf16 in, WAVES*32 bytes of codes out and WAVES*2 scale bytes out.
+//
+// Data movement is shaped for whole cache lines.  Activations arrive by LDS-DMA
+// (global_load_lds_dwordx4: 64 lanes x 16 B land lane-linear in LDS) with one wave instruction
+// covering a contiguous WAVES*128-byte piece of 8/WAVES rows; the MFMA B operands are then read
+// from LDS (lane = token, which would be a whole-wave bank conflict at a row stride of WAVES*128
+// bytes, so the 16-byte chunks of row r are stored XOR-swizzled by r & 15 -- applied on the
+// global side of the DMA, as the LDS side is fixed lane-linear).  Codes and scales go back
+// through LDS so that one store instruction writes full rows of the workgroup tile.
+// STAGES activation tiles rotate through LDS; STAGES-1 of them are in flight while one is used.
+template <int WAVES, int STAGES>
+struct RotqTile {
+    static constexpr int kRowBytes = WAVES * 128;
+    static constexpr int kChunks = kRowBytes / 16;          // 16-byte chunks per row (= lanes per row)
+    static constexpr int kRowsPerInstr = 64 / kChunks;      // WAVES = 8: 1, WAVES = 4: 2
+    static constexpr int kStageBytes = 32 * kRowBytes;
+    static constexpr int kCodeRowBytes = WAVES * 32;
+    static constexpr int kCodeChunks = kCodeRowBytes / 16;  // = WAVES * 2
+    static constexpr int kScaleRowBytes = WAVES * 2;
+    static constexpr int kInBytes = STAGES * kStageBytes;
+    static constexpr int kCodesOff = kInBytes;
+    static constexpr int kScalesOff = kCodesOff + 32 * kCodeRowBytes;
+    static constexpr int kLdsBytes = kScalesOff + 32 * 16;  // scale rows padded to 16 bytes
+    static_assert(kChunks >= 16 && kChunks <= 64, "2 <= WAVES <= 8");
+};
+
+template <int WAVES, int STAGES>
+__device__ __forceinline__ void issue_tile_loads(const RotqParams& p, uint8_t* lds, int stage, int tile, int chunk0,
+                                                 int wave, int lane) {
+    using TL = RotqTile<WAVES, STAGES>;
+    const int nchunk16 = p.G * 4;                            // 16-byte chunks in a full row of X
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int q = wave * 4 + i;                          // instruction index within the tile
+        const int r = q * TL::kRowsPerInstr + lane / TL::kChunks;   // token row within the tile
+        const int pos = lane % TL::kChunks;                  // chunk position in LDS
+        int gch = chunk0 + (pos ^ (r & 15));                 // chunk of the row that belongs there
+        if (gch >= nchunk16) gch = chunk0;                   // ragged last column chunk: any valid address
+        int row = tile * 32 + r;
+        if (row >= p.rows) row = p.rows - 1;                 // ragged last tile
+        const uint16_t* g = p.x + (int64_t)row * p.ldx + (int64_t)gch * 8;
+        __builtin_amdgcn_global_load_lds((global_void_ptr)g, (lds_void_ptr)(lds + stage * TL::kStageBytes + q * 1024),
+                                         16, 0, 0);
+    }
+}
+
+template <int WAVES, int STAGES>
+__global__ __launch_bounds__(WAVES * 64) void rotq_kernel(RotqParams p) {
+    using TL = RotqTile<WAVES, STAGES>;
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     int logical;
     logical_workgroup(logical);
     const int chunk = logical / p.ngroups;
@@ -121,87 +216,141 @@ __global__ __launch_bounds__(kRotqWaves * 64) void rotq_kernel(RotqParams p) {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int c = lane & 31, h = lane >> 5;
+    const uint32_t lds_base = lds_offset(lds);
 
-    const int j0 = (chunk * kRotqWaves + wave) * kBlocksPerWave;
-    if (j0 >= p.G) return;
-    const bool two = (j0 + 1) < p.G;
-    const int j1 = two ? j0 + 1 : j0;
+    // every wave stays to the end (barriers, cooperative loads and stores); waves past the last
+    // block compute on a clamped block and their outputs are masked
+    const int jb = chunk * WAVES * 2;                        // first block of the workgroup
+    int j0 = jb + wave * 2, j1 = j0 + 1;
+    if (j0 >= p.G) j0 = p.G - 1;
+    if (j1 >= p.G) j1 = p.G - 1;
 
     const int tile0 = tg * p.tiles_per_wg;
     int tile1 = tile0 + p.tiles_per_wg;
     if (tile1 > p.ntiles) tile1 = p.ntiles;
-    if (tile0 >= tile1) return;
+    const int chunk0 = jb * 4;                               // first 16-byte chunk of X rows for this workgroup
 
-    const int last_row = p.rows - 1;
-    const int64_t Kh = (int64_t)p.G * 16;   // code bytes per row
-
-    // first tile's activations go out before the R blocks are fetched and split
-    uint4 xn[2][2];
-    {
-        int row = tile0 * 32 + c;
-        if (row > last_row) row = last_row;
-        const uint16_t* xr = p.x + (int64_t)row * p.ldx + 8 * h;
-        xn[0][0] = *(const uint4*)(xr + 32 * j0);
-        xn[0][1] = *(const uint4*)(xr + 32 * j0 + 16);
-        xn[1][0] = *(const uint4*)(xr + 32 * j1);
-        xn[1][1] = *(const uint4*)(xr + 32 * j1 + 16);
-    }
+    constexpr int P = STAGES - 1;                            // tiles in flight
     RotOperand op0, op1;
     load_rot_operand(p.R + (int64_t)j0 * p.r_stride, c, h, op0);
     load_rot_operand(p.R + (int64_t)j1 * p.r_stride, c, h, op1);
+#pragma unroll
+    for (int d = 0; d < P; ++d)
+        if (tile0 + d < tile1) issue_tile_loads<WAVES, STAGES>(p, lds, d, tile0 + d, chunk0, wave, lane);
 
+    int stage = 0;
     for (int tile = tile0; tile < tile1; ++tile) {
-        uint4 xc[2][2] = {{xn[0][0], xn[0][1]}, {xn[1][0], xn[1][1]}};
-        if (tile + 1 < tile1) {
-            int row = (tile + 1) * 32 + c;
-            if (row > last_row) row = last_row;
-            const uint16_t* xr = p.x + (int64_t)row * p.ldx + 8 * h;
-            xn[0][0] = *(const uint4*)(xr + 32 * j0);
-            xn[0][1] = *(const uint4*)(xr + 32 * j0 + 16);
-            xn[1][0] = *(const uint4*)(xr + 32 * j1);
-            xn[1][1] = *(const uint4*)(xr + 32 * j1 + 16);
+        // keep P tiles in flight, then wait for this tile only: LDS-DMA loads complete in issue
+        // order and every wave issues exactly 4 per tile, so "at most 4 * (tiles issued after this
+        // one)" outstanding means this tile has landed (stores issued in between only make the
+        // wait stricter).
+        int pre_stage = stage + P;
+        if (pre_stage >= STAGES) pre_stage -= STAGES;
+        const int ahead = tile1 - 1 - tile;                  // tiles after this one
+        if (ahead >= P) {
+            issue_tile_loads<WAVES, STAGES>(p, lds, pre_stage, tile + P, chunk0, wave, lane);
+            wait_vmcnt<4 * P>();
+        } else if (P >= 3 && ahead == 2) {
+            wait_vmcnt<8>();
+        } else if (P >= 2 && ahead == 1) {
+            wait_vmcnt<4>();
+        } else {
+            wait_vmcnt<0>();
         }
-        f32x16 acc0 = rotate_tile(op0, xc[0]);
-        f32x16 acc1 = rotate_tile(op1, xc[1]);
+        __builtin_amdgcn_s_barrier();                        // all waves' pieces of this tile are in LDS
+
+        const uint32_t in = lds_base + stage * TL::kStageBytes + c * TL::kRowBytes;
+        u32x4 x0[2], x1[2];
+        const int cw = wave * 8 + h;                         // chunk of (block 0, k-step 0) for this lane
+        lds_read4_b128(in + (((cw) ^ (c & 15)) << 4), in + (((cw + 2) ^ (c & 15)) << 4),
+                       in + (((cw + 4) ^ (c & 15)) << 4), in + (((cw + 6) ^ (c & 15)) << 4),
+                       x0[0], x0[1], x1[0], x1[1]);
+
+        f32x16 acc0 = rotate_tile(op0, x0);
+        f32x16 acc1 = rotate_tile(op1, x1);
         uint2 o0, o1;
         uint32_t byte0 = quantize_group(acc0, o0);
         uint32_t byte1 = quantize_group(acc1, o1);
 
-        const int row = tile * 32 + c;
-        if (row <= last_row) {
-            uint8_t* cr = p.codes + (int64_t)row * Kh + 8 * h;
-            *(uint2*)(cr + 16 * j0) = o0;
-            if (two) *(uint2*)(cr + 16 * j1) = o1;
-            // lower half-wave writes block j0's scale, upper half-wave block j1's
-            if (h == 0) p.scales[(int64_t)row * p.G + j0] = (uint8_t)byte0;
-            else if (two) p.scales[(int64_t)row * p.G + j1] = (uint8_t)byte1;
-            if (p.ydbg) {
+        // stage the outputs: codes [token][WAVES*2 chunks of 16 B], chunk index swizzled by the token
+        const uint32_t oc = lds_base + TL::kCodesOff + c * TL::kCodeRowBytes + 8 * h;
+        lds_write_b64(oc + (((wave * 2) ^ (c & 15) & (TL::kCodeChunks - 1)) << 4), o0);
+        lds_write_b64(oc + (((wave * 2 + 1) ^ (c & 15) & (TL::kCodeChunks - 1)) << 4), o1);
+        lds_write_b8(lds_base + TL::kScalesOff + c * 16 + wave * 2 + h, h ? byte1 : byte0);
+
+        if (p.ydbg) {
+            const int row = tile * 32 + c;
+            if (row < p.rows) {
                 float* yr = p.ydbg + (int64_t)row * p.G * 32 + 4 * h;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    *(float4*)(yr + 32 * j0 + 8 * q) = make_float4(acc0[4 * q], acc0[4 * q + 1], acc0[4 * q + 2], acc0[4 * q + 3]);
-                    if (two) *(float4*)(yr + 32 * j1 + 8 * q) = make_float4(acc1[4 * q], acc1[4 * q + 1], acc1[4 * q + 2], acc1[4 * q + 3]);
+                    if (jb + wave * 2 < p.G)
+                        *(float4*)(yr + 32 * j0 + 8 * q) = make_float4(acc0[4 * q], acc0[4 * q + 1], acc0[4 * q + 2], acc0[4 * q + 3]);
+                    if (jb + wave * 2 + 1 < p.G)
+                        *(float4*)(yr + 32 * j1 + 8 * q) = make_float4(acc1[4 * q], acc1[4 * q + 1], acc1[4 * q + 2], acc1[4 * q + 3]);
                 }
             }
         }
+        lds_barrier();                                       // outputs of all waves are staged
+
+        // codes: thread i stores 16 bytes; one wave instruction covers 64 / (WAVES*2) full rows
+        {
+            const int r = threadIdx.x / TL::kCodeChunks;     // 0..31
+            const int ch = threadIdx.x % TL::kCodeChunks;
+            const int row = tile * 32 + r;
+            if (row < p.rows && jb + ch < p.G) {
+                u32x4 v = lds_read_b128(lds_base + TL::kCodesOff + r * TL::kCodeRowBytes + ((ch ^ (r & 15) & (TL::kCodeChunks - 1)) << 4));
+                *(u32x4*)(p.codes + ((int64_t)row * p.G + jb + ch) * 16) = v;
+            }
+        }
+        // scales: one row of the tile per lane of wave 0
+        if (threadIdx.x < 32) {
+            const int row = tile * 32 + threadIdx.x;
+            if (row < p.rows) {
+                const uint32_t sr = lds_base + TL::kScalesOff + threadIdx.x * 16;
+                uint8_t* dst = p.scales + (int64_t)row * p.G + jb;
+                u32x4 v = lds_read_b128(sr);
+                if (jb + TL::kScaleRowBytes <= p.G && (((uintptr_t)dst) & (TL::kScaleRowBytes - 1)) == 0) {
+                    if (TL::kScaleRowBytes == 16) *(u32x4*)dst = v;
+                    else if (TL::kScaleRowBytes == 8) *(uint2*)dst = make_uint2(v[0], v[1]);
+                    else *(uint32_t*)dst = v[0];
+                } else {
+#pragma unroll
+                    for (int b = 0; b < TL::kScaleRowBytes; ++b)
+                        if (jb + b < p.G) dst[b] = (uint8_t)(v[b / 4] >> (8 * (b % 4)));
+                }
+            }
+        }
+        stage = stage + 1 == STAGES ? 0 : stage + 1;
     }
 }
+
+constexpr int kRotqStages = 4;
 
 void plan_rotq(RotqParams& p) {
     p.ntiles = (p.rows + 31) / 32;
     p.nchunks = (p.G + kBlocksPerWG - 1) / kBlocksPerWG;
-    // Aim for one resident round: about 4 workgroups of 8 waves per CU.
-    const int64_t slots = (int64_t)kNumCU * 4;
-    int64_t units = (int64_t)p.ntiles * p.nchunks;
-    int tpw = (int)((units + slots - 1) / slots);
-    if (tpw < 1) tpw = 1;
-    p.tiles_per_wg = tpw;
-    p.ngroups = (p.ntiles + tpw - 1) / tpw;
+    // One resident round: each workgroup keeps its R blocks in registers and walks as many token
+    // tiles as the problem allows, so the fetch and split of R is amortised.
+    const int64_t slots = (int64_t)kNumCU * kRotqWGPerCU;
+    int groups = (int)(slots / p.nchunks);
+    if (groups < 1) groups = 1;
+    if (groups > p.ntiles) groups = p.ntiles;
+    p.tiles_per_wg = (p.ntiles + groups - 1) / groups;
+    p.ngroups = (p.ntiles + p.tiles_per_wg - 1) / p.tiles_per_wg;
 }
 
 hipError_t launch_rotq(const RotqParams& p, hipStream_t stream) {
+    using TL = RotqTile<kRotqWaves, kRotqStages>;
+    static std::atomic<int> configured{0};
+    auto kern = rotq_kernel<kRotqWaves, kRotqStages>;
+    if (!configured.load(std::memory_order_acquire)) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::kLdsBytes);
+        if (e != hipSuccess) return e;
+        configured.store(1, std::memory_order_release);
+    }
     dim3 grid((unsigned)((int64_t)p.nchunks * p.ngroups)), block(kRotqWaves * 64);
-    hipLaunchKernelGGL(rotq_kernel, grid, block, 0, stream, p);
+    hipLaunchKernelGGL(kern, grid, block, TL::kLdsBytes, stream, p);
     return hipGetLastError();
 }
 
