@@ -76,22 +76,22 @@ def main():
             x0_bits, w0_bits, R0 = xb, wb, R
         x, Rd = dev_bf16(xb), torch.from_numpy(R).to(dev)
         w = dev_bf16(wb)
-        bc, bs = duqpp.quantize_weights(w, Rd)            # offline weight transform, not timed
+        bc, bs = duqpp.quantize_weights_tiled(w, Rd)      # offline weight transform (tiled layout), not timed
         del w
+        cb, sb = duqpp.tiled_bytes(T, K)
         sets.append(dict(
             x=x, R=Rd, bc=bc, bs=bs,
-            ac=torch.empty((T, K // 2), dtype=torch.uint8, device=dev),
-            asc=torch.empty((T, G), dtype=torch.uint8, device=dev),
+            ac=torch.empty(cb, dtype=torch.uint8, device=dev),
+            asc=torch.empty(sb, dtype=torch.uint8, device=dev),
             y=torch.empty((T, N), dtype=torch.bfloat16 if cfg["out"] == "bf16" else torch.float32, device=dev)))
-    ws_bytes = duqpp.gemm_workspace_bytes(T, N, K, False)
-    ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=dev) if ws_bytes else None
     torch.cuda.synchronize()
 
+    # the timed path: activations rotated + quantised into the tiled operand layout, then the tiled GEMM
     def rotq(s):
-        duqpp.rotate_quantize(s["x"], s["R"], out=(s["ac"], s["asc"]))
+        duqpp.rotate_quantize_tiled(s["x"], s["R"], out=(s["ac"], s["asc"]))
 
     def gemm(s):
-        duqpp.mxfp4_gemm(s["ac"], s["asc"], s["bc"], s["bs"], out_dtype=out_dtype, out=s["y"], workspace=ws)
+        duqpp.mxfp4_gemm_tiled(s["ac"], s["asc"], s["bc"], s["bs"], T, N, K, out_dtype=out_dtype, out=s["y"])
 
     def step(i):
         s = sets[i % nsets]
@@ -141,7 +141,8 @@ def main():
         "dtype": "mxfp4 (E2M1 codes + E8M0 scales; fp32 rotation and accumulation)",
         "data": "synthetic",
         "config": {"workload": args.config, "T": T, "K": K, "N": N, "output": cfg["out"],
-                   "buffer_sets": nsets, "rotation_blocks": G},
+                   "buffer_sets": nsets, "rotation_blocks": G,
+                   "operand_layout": "tiled"},
         "components": {
             "rotate_quantize": {"us": round(rotq_us, 2), "GB/s": round(rotq_gbps, 1),
                                 "frac_hbm_peak": round(rotq_gbps / HBM_PEAK_GBPS, 4)},
@@ -167,7 +168,8 @@ def main():
             threads = os.cpu_count() or 1
         Ts = min(T, 256)
         s0 = sets[0]
-        bc_h, bs_h = s0["bc"].cpu().numpy(), s0["bs"].cpu().numpy()
+        bc_rm, bs_rm = duqpp.untile_operand(s0["bc"], s0["bs"], N, K)       # row-major view of the weights for the oracle
+        bc_h, bs_h = bc_rm.cpu().numpy(), bs_rm.cpu().numpy()
         c0 = time.perf_counter()
         a_codes, a_scales, _ = oracle.pipeline.rotate_quantize(x0_bits[:Ts], R0)
         y_ref = oracle.linear.mxfp4_gemm(a_codes, a_scales, bc_h, bs_h)
@@ -181,11 +183,12 @@ def main():
         gemm(s0)
         torch.cuda.synchronize()
         y_dev = s0["y"][:Ts].float().cpu().numpy()
-        a_dev = s0["ac"][:Ts].cpu().numpy()
+        ac_rm, as_rm = duqpp.untile_operand(s0["ac"], s0["asc"], T, K)
+        a_dev = ac_rm[:Ts].cpu().numpy()
         result["parity"] = {
             "codes_equal_fraction": float(np.mean(a_dev == a_codes)),
             "gemm_rel_fro_vs_oracle_on_own_codes": float(
-                np.linalg.norm(y_dev - oracle.linear.mxfp4_gemm(a_dev, s0["asc"][:Ts].cpu().numpy(), bc_h, bs_h))
+                np.linalg.norm(y_dev - oracle.linear.mxfp4_gemm(a_dev, as_rm[:Ts].cpu().numpy(), bc_h, bs_h))
                 / np.linalg.norm(y_ref)),
             "note": "bf16 output rounding (2^-9) bounds the second figure" if cfg["out"] == "bf16" else ""}
     print(json.dumps(result))

@@ -119,6 +119,54 @@ int duqpp_rotq_gemm(const void* x_bf16, int64_t ldx, const float* R, int64_t n_r
 int duqpp_quantize_f32_dbg(const float* y, int64_t rows, int64_t K, int64_t ldy,
                            uint8_t* codes, uint8_t* scales, void* stream);
 
+/*
+ * ---- Tiled operand layout: the fast path ---------------------------------------------------
+ * The row-major [rows, K/2] + [rows, K/32] form above is the interchange contract.  The GEMM's
+ * matrix-core operand for one lane is one MXFP4 group of one row (16 code bytes + 1 scale byte),
+ * so the kernels run fastest on a layout that keeps the 32 rows of a row tile adjacent per group.
+ * With RT = ceil(rows / 32) and GP = ceil((K/32) / 8) * 8:
+ *     codes_t   uint8 [RT][GP][32][16]        16 code bytes of (row 32 rt + r, group j) at
+ *                                             ((rt * GP + j) * 32 + r) * 16
+ *     scales_t  uint8 [RT][GP/8][2][32][4]    scale of (row 32 rt + r, group j) at
+ *                                             (((rt * GP/8 + j/8) * 2 + (j%8)/4) * 32 + r) * 4 + j%4
+ * Padding rows and groups hold code 0 and scale 127.  Sizes come from duqpp_tiled_bytes; bases
+ * must be 256-byte aligned.  The *_tiled entry points compute exactly what their row-major
+ * counterparts compute (Eq. 5 / Eq. 2); only the placement of the bytes differs.
+ */
+
+/* Host, pure: bytes of the tiled codes and scales of a [rows, K] operand (either pointer may be null). */
+int duqpp_tiled_bytes(int64_t rows, int64_t K, size_t* codes_bytes, size_t* scales_bytes);
+
+/* Row-major -> tiled (writes the padding too) and back.  Pure byte permutations. */
+int duqpp_tile_operand(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K,
+                       uint8_t* codes_t, uint8_t* scales_t, void* stream);
+int duqpp_untile_operand(const uint8_t* codes_t, const uint8_t* scales_t, int64_t rows, int64_t K,
+                         uint8_t* codes, uint8_t* scales, void* stream);
+
+/* duqpp_quantize_weights / duqpp_rotate_quantize with tiled outputs. */
+int duqpp_quantize_weights_tiled(const void* w_bf16, int64_t N, int64_t K, int64_t ldw,
+                                 const float* R, int64_t n_rblocks,
+                                 uint8_t* w_codes_t, uint8_t* w_scales_t, void* stream);
+int duqpp_rotate_quantize_tiled(const void* x_bf16, int64_t T, int64_t K, int64_t ldx,
+                                const float* R, int64_t n_rblocks,
+                                uint8_t* x_codes_t, uint8_t* x_scales_t, void* stream);
+
+/* duqpp_mxfp4_gemm on tiled operands (no workspace). */
+int duqpp_mxfp4_gemm_tiled(const uint8_t* a_codes_t, const uint8_t* a_scales_t,
+                           const uint8_t* b_codes_t, const uint8_t* b_scales_t,
+                           int64_t T, int64_t N, int64_t K,
+                           void* y, int out_dtype, int64_t ldy, void* stream);
+
+/*
+ * duqpp_rotq_gemm with tiled weights.  workspace: at least the two sizes duqpp_tiled_bytes(T, K)
+ * reports, each rounded up to 256, 256-byte aligned.
+ */
+int duqpp_rotq_gemm_tiled(const void* x_bf16, int64_t ldx, const float* R, int64_t n_rblocks,
+                          const uint8_t* b_codes_t, const uint8_t* b_scales_t,
+                          int64_t T, int64_t N, int64_t K,
+                          void* y, int out_dtype, int64_t ldy,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
 /* Host, pure: scratch bytes duqpp_mxfp4_gemm (fused = 0) or duqpp_rotq_gemm (fused = 1) needs. */
 size_t duqpp_gemm_workspace_bytes(int64_t T, int64_t N, int64_t K, int fused);
 
@@ -133,7 +181,8 @@ int duqpp_validate_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
                               const uint8_t* b_codes, const uint8_t* b_scales,
                               int64_t T, int64_t N, int64_t K,
                               const void* y, int out_dtype, int64_t ldy,
-                              const void* workspace, size_t workspace_bytes, int fused);
+                              const void* workspace, size_t workspace_bytes,
+                              int fused /* 0 separate, 1 fused, 2 tiled operands (no workspace) */);
 
 /* Static strings. */
 const char* duqpp_status_string(int status);

@@ -10,6 +10,13 @@ from .binding import (  # noqa: F401
     lib,
     library_path,
     mxfp4_gemm,
+    mxfp4_gemm_tiled,
+    quantize_weights_tiled,
+    rotate_quantize_tiled,
+    rotq_gemm_tiled,
+    tile_operand,
+    tiled_bytes,
+    untile_operand,
     quantize_f32_dbg,
     quantize_weights,
     rotate_quantize,

@@ -38,6 +38,17 @@ def _load():
     L.duqpp_gemm_workspace_bytes.restype = sz
     L.duqpp_validate_rotate_quantize.argtypes = [vp, i64, i64, i64, fp, i64, u8p, u8p]
     L.duqpp_validate_mxfp4_gemm.argtypes = [u8p, u8p, u8p, u8p, i64, i64, i64, vp, ci, i64, vp, sz, ci]
+    szp = ctypes.POINTER(ctypes.c_size_t)
+    L.duqpp_tiled_bytes.argtypes = [i64, i64, szp, szp]
+    L.duqpp_tile_operand.argtypes = [u8p, u8p, i64, i64, u8p, u8p, vp]
+    L.duqpp_untile_operand.argtypes = [u8p, u8p, i64, i64, u8p, u8p, vp]
+    L.duqpp_quantize_weights_tiled.argtypes = [vp, i64, i64, i64, fp, i64, u8p, u8p, vp]
+    L.duqpp_rotate_quantize_tiled.argtypes = [vp, i64, i64, i64, fp, i64, u8p, u8p, vp]
+    L.duqpp_mxfp4_gemm_tiled.argtypes = [u8p, u8p, u8p, u8p, i64, i64, i64, vp, ci, i64, vp]
+    L.duqpp_rotq_gemm_tiled.argtypes = [vp, i64, fp, i64, u8p, u8p, i64, i64, i64, vp, ci, i64, vp, sz, vp]
+    for name in ("duqpp_tiled_bytes", "duqpp_tile_operand", "duqpp_untile_operand", "duqpp_quantize_weights_tiled",
+                 "duqpp_rotate_quantize_tiled", "duqpp_mxfp4_gemm_tiled", "duqpp_rotq_gemm_tiled"):
+        getattr(L, name).restype = ci
     for name in ("duqpp_quantize_weights", "duqpp_rotate_quantize", "duqpp_mxfp4_gemm", "duqpp_rotq_gemm",
                  "duqpp_quantize_f32_dbg", "duqpp_validate_rotate_quantize", "duqpp_validate_mxfp4_gemm"):
         getattr(L, name).restype = ci
@@ -192,3 +203,95 @@ def quantize_f32_dbg(y):
     st = lib.duqpp_quantize_f32_dbg(y.data_ptr(), rows, K, y.stride(0), codes.data_ptr(), scales.data_ptr(), _stream())
     _check(st, "duqpp_quantize_f32_dbg")
     return codes, scales
+
+
+# ---------------------------------------------------------------- tiled operand layout
+def tiled_bytes(rows, K):
+    """(codes bytes, scales bytes) of the tiled form of a [rows, K] operand."""
+    cb, sb = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(lib.duqpp_tiled_bytes(rows, K, ctypes.byref(cb), ctypes.byref(sb)), "duqpp_tiled_bytes")
+    return int(cb.value), int(sb.value)
+
+
+def _tiled_buffers(rows, K, device, out=None):
+    cb, sb = tiled_bytes(rows, K)
+    if out is None:
+        return (torch.empty(cb, dtype=torch.uint8, device=device), torch.empty(sb, dtype=torch.uint8, device=device))
+    c, s = out
+    _dev(c, torch.uint8, "codes_t")
+    _dev(s, torch.uint8, "scales_t")
+    if c.numel() != cb or s.numel() != sb or not c.is_contiguous() or not s.is_contiguous():
+        raise ValueError("bad tiled output tensors")
+    return c, s
+
+
+def tile_operand(codes, scales):
+    _dev(codes, torch.uint8, "codes")
+    _dev(scales, torch.uint8, "scales")
+    rows, K = codes.shape[0], codes.shape[1] * 2
+    ct, st_ = _tiled_buffers(rows, K, codes.device)
+    _check(lib.duqpp_tile_operand(codes.data_ptr(), scales.data_ptr(), rows, K, ct.data_ptr(), st_.data_ptr(), _stream()),
+           "duqpp_tile_operand")
+    return ct, st_
+
+
+def untile_operand(codes_t, scales_t, rows, K):
+    _dev(codes_t, torch.uint8, "codes_t")
+    _dev(scales_t, torch.uint8, "scales_t")
+    codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=codes_t.device)
+    scales = torch.empty((rows, K // 32), dtype=torch.uint8, device=codes_t.device)
+    _check(lib.duqpp_untile_operand(codes_t.data_ptr(), scales_t.data_ptr(), rows, K, codes.data_ptr(), scales.data_ptr(),
+                                    _stream()), "duqpp_untile_operand")
+    return codes, scales
+
+
+def _rows_op_tiled(fn, name, x, R, out):
+    _dev(x, torch.bfloat16, "x")
+    _dev(R, torch.float32, "R")
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be [rows, K] with unit stride along K")
+    rows, K = x.shape
+    ct, st_ = _tiled_buffers(rows, K, x.device, out)
+    _check(fn(x.data_ptr(), rows, K, x.stride(0), R.data_ptr(), _n_rblocks(R), ct.data_ptr(), st_.data_ptr(), _stream()), name)
+    return ct, st_
+
+
+def rotate_quantize_tiled(x, R, out=None):
+    """x bf16 [T, K] -> (codes_t, scales_t): flat uint8 tensors in the tiled operand layout."""
+    return _rows_op_tiled(lib.duqpp_rotate_quantize_tiled, "duqpp_rotate_quantize_tiled", x, R, out)
+
+
+def quantize_weights_tiled(w, R, out=None):
+    return _rows_op_tiled(lib.duqpp_quantize_weights_tiled, "duqpp_quantize_weights_tiled", w, R, out)
+
+
+def mxfp4_gemm_tiled(a_codes_t, a_scales_t, b_codes_t, b_scales_t, T, N, K, out_dtype=F32, out=None):
+    for t, n in ((a_codes_t, "a_codes_t"), (a_scales_t, "a_scales_t"), (b_codes_t, "b_codes_t"), (b_scales_t, "b_scales_t")):
+        _dev(t, torch.uint8, n)
+    if (a_codes_t.numel(), a_scales_t.numel()) != tiled_bytes(T, K) or (b_codes_t.numel(), b_scales_t.numel()) != tiled_bytes(N, K):
+        raise ValueError("operand sizes disagree with T, N, K")
+    y = _out(T, N, out_dtype, a_codes_t.device, out)
+    _check(lib.duqpp_mxfp4_gemm_tiled(a_codes_t.data_ptr(), a_scales_t.data_ptr(), b_codes_t.data_ptr(), b_scales_t.data_ptr(),
+                                      T, N, K, y.data_ptr(), out_dtype, y.stride(0), _stream()), "duqpp_mxfp4_gemm_tiled")
+    return y
+
+
+def rotq_gemm_tiled(x, R, b_codes_t, b_scales_t, N, out_dtype=F32, out=None, workspace=None):
+    _dev(x, torch.bfloat16, "x")
+    _dev(R, torch.float32, "R")
+    _dev(b_codes_t, torch.uint8, "b_codes_t")
+    _dev(b_scales_t, torch.uint8, "b_scales_t")
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be [T, K] with unit stride along K")
+    T, K = x.shape
+    if (b_codes_t.numel(), b_scales_t.numel()) != tiled_bytes(N, K):
+        raise ValueError("weight operand sizes disagree with N, K")
+    y = _out(T, N, out_dtype, x.device, out)
+    cb, sb = tiled_bytes(T, K)
+    need = ((cb + 255) // 256 + (sb + 255) // 256) * 256
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    _check(lib.duqpp_rotq_gemm_tiled(x.data_ptr(), x.stride(0), R.data_ptr(), _n_rblocks(R), b_codes_t.data_ptr(),
+                                     b_scales_t.data_ptr(), T, N, K, y.data_ptr(), out_dtype, y.stride(0),
+                                     workspace.data_ptr(), workspace.numel(), _stream()), "duqpp_rotq_gemm_tiled")
+    return y

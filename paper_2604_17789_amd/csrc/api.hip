@@ -36,10 +36,11 @@ int validate_rows_K(int64_t rows, int64_t K, int64_t ld, int64_t n_rblocks) {
 }
 
 int rotate_quantize_impl(const void* x, int64_t rows, int64_t K, int64_t ldx, const float* R, int64_t n_rblocks,
-                         uint8_t* codes, uint8_t* scales, float* ydbg, void* stream) {
+                         uint8_t* codes, uint8_t* scales, float* ydbg, void* stream, bool tiled = false) {
     int st = duqpp_validate_rotate_quantize(x, rows, K, ldx, R, n_rblocks, codes, scales);
     if (st != DUQPP_OK) return st;
     if (ydbg && !aligned_to(ydbg, 16)) return DUQPP_ERR_ALIGN;
+    if (tiled && (!aligned_to(codes, 256) || !aligned_to(scales, 256))) return DUQPP_ERR_ALIGN;
     st = check_device();
     if (st != DUQPP_OK) return st;
     RotqParams p{};
@@ -52,6 +53,8 @@ int rotate_quantize_impl(const void* x, int64_t rows, int64_t K, int64_t ldx, co
     p.codes = codes;
     p.scales = scales;
     p.ydbg = ydbg;
+    p.tiled = tiled ? 1 : 0;
+    p.GP = (int)tiled_groups(K / 32);
     plan_rotq(p);
     return launch_rotq(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
 }
@@ -87,6 +90,7 @@ int duqpp_validate_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales, c
     if (!aligned_to(b_codes, 16)) return DUQPP_ERR_ALIGN;
     if (!fused && !aligned_to(a_codes, 16)) return DUQPP_ERR_ALIGN;
     if (!aligned_to(y, out_dtype == DUQPP_F32 ? 4 : 2)) return DUQPP_ERR_ALIGN;
+    if (fused == 2) return DUQPP_OK;   // tiled operands: no workspace
     size_t need = duqpp_gemm_workspace_bytes(T, N, K, fused);
     if (need > 0) {
         if (!workspace || workspace_bytes < need) return DUQPP_ERR_WORKSPACE;
@@ -159,6 +163,83 @@ int duqpp_quantize_f32_dbg(const float* y, int64_t rows, int64_t K, int64_t ldy,
     if (st != DUQPP_OK) return st;
     QuantDbgParams p{y, ldy, (int)rows, (int)(K / 32), codes, scales};
     return launch_quant_dbg(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
+}
+
+int duqpp_tiled_bytes(int64_t rows, int64_t K, size_t* codes_bytes, size_t* scales_bytes) {
+    if (rows < 1 || K < 32 || (K % 32) != 0 || rows > (int64_t)1 << 30 || K > (int64_t)1 << 30) return DUQPP_ERR_SHAPE;
+    if (codes_bytes) *codes_bytes = tiled_codes_bytes(rows, K / 32);
+    if (scales_bytes) *scales_bytes = tiled_scales_bytes(rows, K / 32);
+    return DUQPP_OK;
+}
+
+static int layout_call(const uint8_t* src_c, const uint8_t* src_s, int64_t rows, int64_t K, uint8_t* dst_c,
+                       uint8_t* dst_s, void* stream, bool to_tiled) {
+    if (!src_c || !src_s || !dst_c || !dst_s) return DUQPP_ERR_NULL;
+    int st = validate_rows_K(rows, K, K, 1);
+    if (st != DUQPP_OK) return st;
+    const uint8_t* tc = to_tiled ? dst_c : src_c;
+    const uint8_t* ts = to_tiled ? dst_s : src_s;
+    const uint8_t* rc = to_tiled ? src_c : dst_c;
+    if (!aligned_to(tc, 256) || !aligned_to(ts, 256) || !aligned_to(rc, 16)) return DUQPP_ERR_ALIGN;
+    st = check_device();
+    if (st != DUQPP_OK) return st;
+    LayoutParams p{src_c, src_s, dst_c, dst_s, (int)rows, (int)(K / 32), (int)tiled_groups(K / 32)};
+    hipError_t e = to_tiled ? launch_tile(p, static_cast<hipStream_t>(stream)) : launch_untile(p, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
+}
+
+int duqpp_tile_operand(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t K, uint8_t* codes_t,
+                       uint8_t* scales_t, void* stream) {
+    return layout_call(codes, scales, rows, K, codes_t, scales_t, stream, true);
+}
+
+int duqpp_untile_operand(const uint8_t* codes_t, const uint8_t* scales_t, int64_t rows, int64_t K, uint8_t* codes,
+                         uint8_t* scales, void* stream) {
+    return layout_call(codes_t, scales_t, rows, K, codes, scales, stream, false);
+}
+
+int duqpp_quantize_weights_tiled(const void* w_bf16, int64_t N, int64_t K, int64_t ldw, const float* R,
+                                 int64_t n_rblocks, uint8_t* w_codes_t, uint8_t* w_scales_t, void* stream) {
+    return rotate_quantize_impl(w_bf16, N, K, ldw, R, n_rblocks, w_codes_t, w_scales_t, nullptr, stream, true);
+}
+
+int duqpp_rotate_quantize_tiled(const void* x_bf16, int64_t T, int64_t K, int64_t ldx, const float* R,
+                                int64_t n_rblocks, uint8_t* x_codes_t, uint8_t* x_scales_t, void* stream) {
+    return rotate_quantize_impl(x_bf16, T, K, ldx, R, n_rblocks, x_codes_t, x_scales_t, nullptr, stream, true);
+}
+
+int duqpp_mxfp4_gemm_tiled(const uint8_t* a_codes_t, const uint8_t* a_scales_t, const uint8_t* b_codes_t,
+                           const uint8_t* b_scales_t, int64_t T, int64_t N, int64_t K, void* y, int out_dtype,
+                           int64_t ldy, void* stream) {
+    int st = duqpp_validate_mxfp4_gemm(a_codes_t, a_scales_t, b_codes_t, b_scales_t, T, N, K, y, out_dtype, ldy,
+                                       nullptr, 0, 2);
+    if (st != DUQPP_OK) return st;
+    if (!aligned_to(a_codes_t, 256) || !aligned_to(a_scales_t, 256) || !aligned_to(b_codes_t, 256) ||
+        !aligned_to(b_scales_t, 256))
+        return DUQPP_ERR_ALIGN;
+    st = check_device();
+    if (st != DUQPP_OK) return st;
+    TiledGemmParams p{a_codes_t, a_scales_t, b_codes_t, b_scales_t, (int)T, (int)N, (int)tiled_groups(K / 32),
+                      y, ldy, out_dtype == DUQPP_BF16};
+    return launch_gemm_tiled(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
+}
+
+int duqpp_rotq_gemm_tiled(const void* x_bf16, int64_t ldx, const float* R, int64_t n_rblocks,
+                          const uint8_t* b_codes_t, const uint8_t* b_scales_t, int64_t T, int64_t N, int64_t K,
+                          void* y, int out_dtype, int64_t ldy, void* workspace, size_t workspace_bytes,
+                          void* stream) {
+    if (!x_bf16 || !R || !b_codes_t || !b_scales_t || !y) return DUQPP_ERR_NULL;
+    int st = validate_rows_K(T, K, ldx, n_rblocks);
+    if (st != DUQPP_OK) return st;
+    const size_t cb = (tiled_codes_bytes(T, K / 32) + 255) & ~(size_t)255;
+    const size_t sb = (tiled_scales_bytes(T, K / 32) + 255) & ~(size_t)255;
+    if (!workspace || workspace_bytes < cb + sb) return DUQPP_ERR_WORKSPACE;
+    if (!aligned_to(workspace, 256)) return DUQPP_ERR_ALIGN;
+    uint8_t* a_codes = static_cast<uint8_t*>(workspace);
+    uint8_t* a_scales = a_codes + cb;
+    st = rotate_quantize_impl(x_bf16, T, K, ldx, R, n_rblocks, a_codes, a_scales, nullptr, stream, true);
+    if (st != DUQPP_OK) return st;
+    return duqpp_mxfp4_gemm_tiled(a_codes, a_scales, b_codes_t, b_scales_t, T, N, K, y, out_dtype, ldy, stream);
 }
 
 const char* duqpp_status_string(int status) {

@@ -20,8 +20,10 @@ struct RotqParams {
     int G;               // K / 32
     const float* R;      // [n_rblocks, 32, 32]
     int r_stride;        // floats between consecutive blocks of R (0 when one block is shared)
-    uint8_t* codes;      // [rows, K/2]
-    uint8_t* scales;     // [rows, G]
+    uint8_t* codes;      // [rows, K/2], or the tiled codes when tiled != 0
+    uint8_t* scales;     // [rows, G], or the tiled scales
+    int tiled;           // output placement
+    int GP;              // groups padded to a multiple of 8 (tiled layout)
     float* ydbg;         // nullable [rows, K]
     int ntiles;          // ceil(rows / 32)
     int tiles_per_wg;
@@ -46,5 +48,38 @@ struct GemmParams {
 };
 hipError_t launch_gemm(const GemmParams& p, hipStream_t stream);
 size_t gemm_workspace_bytes(int64_t T, int64_t N, int64_t K);
+
+}  // namespace duqpp
+
+// ---- tiled operand layout (layout.hip, gemm_tiled.hip) ----------------------------------
+// An MXFP4 operand with `rows` rows and G groups, padded to RT = ceil(rows/32) row tiles and
+// GP = ceil(G/8)*8 groups:
+//   codes   [RT][GP][32 rows][16 bytes]            one group of one row = 16 contiguous bytes,
+//                                                  the 32 rows of a tile adjacent (512 B), then the next group
+//   scales  [RT][GP/8][2][32 rows][4 bytes]        byte b of the word at [rt][q][g][r] is the scale of
+//                                                  row 32 rt + r, group 8 q + 4 g + b
+// Padding rows and groups hold code 0 and scale 127 (= 1.0), so they contribute exact zeros.
+namespace duqpp {
+
+inline int64_t tiled_row_tiles(int64_t rows) { return (rows + 31) / 32; }
+inline int64_t tiled_groups(int64_t G) { return (G + 7) / 8 * 8; }
+inline size_t tiled_codes_bytes(int64_t rows, int64_t G) { return (size_t)tiled_row_tiles(rows) * tiled_groups(G) * 512; }
+inline size_t tiled_scales_bytes(int64_t rows, int64_t G) { return (size_t)tiled_row_tiles(rows) * tiled_groups(G) * 32; }
+
+struct LayoutParams {
+    const uint8_t* src_codes; const uint8_t* src_scales;
+    uint8_t* dst_codes; uint8_t* dst_scales;
+    int rows, G, GP;
+};
+hipError_t launch_tile(const LayoutParams& p, hipStream_t stream);     // row-major -> tiled (writes the padding too)
+hipError_t launch_untile(const LayoutParams& p, hipStream_t stream);   // tiled -> row-major
+
+struct TiledGemmParams {
+    const uint8_t* a_codes; const uint8_t* a_scales;   // tiled, T rows
+    const uint8_t* b_codes; const uint8_t* b_scales;   // tiled, N rows
+    int T, N, GP;
+    void* y; int64_t ldy; int out_bf16;
+};
+hipError_t launch_gemm_tiled(const TiledGemmParams& p, hipStream_t stream);
 
 }  // namespace duqpp

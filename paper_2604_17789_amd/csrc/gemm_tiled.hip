@@ -1,0 +1,327 @@
+// W4A4 MXFP4 GEMM (the Q(X^) . Q(W^) product of the paper's Eq. 5) for operands in the tiled
+// layout, on gfx950's block-scaled matrix cores (v_mfma_scale_f32_32x32x64_f8f6f4, FP4 x FP4).
+//
+// Shape of the kernel
+//   workgroup  4 waves (one per SIMD) as 2 x 2, output tile 128 (tokens) x 256 (output channels);
+//              each wave owns 64 x 128 = 2 x 4 MFMA tiles = 128 fp32 accumulators per lane.
+//   K loop     steps of 256 (8 MXFP4 groups).  The codes of a step, (4 + 8) row tiles x 4 KiB, and
+//              their scale words, 12 x 256 B, go from global memory straight into LDS by LDS-DMA
+//              (each code transfer moves one contiguous KiB); three such stages rotate, two in
+//              flight while one is consumed.
+//   operands   in the tiled layout the 16 code bytes of (row r, group j) of a row tile sit at
+//              (j * 32 + r) * 16, so the FP4 operand of lane (r, g) for MFMA i of a step -- group
+//              4 g + i of row r -- is one ds_read_b128 and 32 lanes read 512 contiguous bytes.
+//   scales     lane (r, g) needs the four E8M0 bytes of groups 4 g .. 4 g + 3: one 32-bit word,
+//              stored lane-linear per (row tile, step); the four MFMAs of a step select bytes
+//              0..3 of it.
+// K is a summation index, so feeding groups to the instruction in this permuted order changes
+// nothing but the order of the fp32 additions.
+//
+// The LDS-DMA transfers are issued from asm statements and their completion is awaited by hand
+// (s_waitcnt vmcnt before the workgroup barrier): were they visible to the compiler as LDS writes, it
+// would drain the whole DMA queue before every LDS read it cannot disambiguate, i.e. serialise the
+// pipeline.  No other vector-memory load is issued inside the K loop, so the compiler places no
+// vmcnt wait of its own there; LDS reads and MFMAs are ordinary code with compiler-managed waits.
+#include <atomic>
+#include <type_traits>
+
+#include "duqpp_internal.h"
+
+namespace duqpp {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* global_void_ptr;
+
+constexpr int kBM = 128, kBN = 256;
+constexpr int kMT = kBM / 32, kNT = kBN / 32;           // row tiles of A / B per workgroup
+constexpr int kTileStepBytes = 8 * 512;                 // one row tile, one K step (8 groups)
+constexpr int kStageBytes = (kMT + kNT) * kTileStepBytes + 4 * 1024;   // codes + scale words
+constexpr int kStages = 3;
+constexpr int kGemmLdsBytes = kStages * kStageBytes;    // 159744 of the CU's 163840
+constexpr int kGroupM = 4;                              // M tiles per group in the workgroup ordering
+
+constexpr int kScaleRegionBytes = 4 * 1024;               // 12 x 256 B of scale words + 1 KiB of padding
+constexpr int kScalesOff = (kMT + kNT) * kTileStepBytes;  // scale words follow the codes in a stage
+
+struct Frags {
+    u32x4 a[2], b[4];
+};
+
+struct Scales {
+    uint32_t a[2], b[4];
+};
+
+// M0 carries the LDS destination of an LDS-DMA transfer; the compiler reserves the register but
+// has no use for it in this kernel, and the clobber tells it the value does not survive.
+#pragma clang diagnostic ignored "-Winline-asm"
+
+// Four KiB-sized LDS-DMA transfers: global [src, src + 4096) (64 lanes x 16 B per transfer) to LDS
+// [lds_dst, lds_dst + 4096).  The immediate offset advances both addresses.
+__device__ __forceinline__ void dma_4k(const uint8_t* src_lane, uint32_t lds_dst) {
+    asm volatile(
+        "s_mov_b32 m0, %1\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %0, off\n\t"
+        "global_load_lds_dwordx4 %0, off offset:1024\n\t"
+        "global_load_lds_dwordx4 %0, off offset:2048\n\t"
+        "global_load_lds_dwordx4 %0, off offset:3072"
+        :
+        : "v"(src_lane), "s"(lds_dst)
+        : "memory", "m0");
+}
+
+__device__ __forceinline__ void dma_1k(const uint8_t* src_lane, uint32_t lds_dst) {
+    asm volatile(
+        "s_mov_b32 m0, %1\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %0, off"
+        :
+        : "v"(src_lane), "s"(lds_dst)
+        : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__device__ __forceinline__ void workgroup_barrier() {
+    asm volatile("s_barrier" ::: "memory");
+}
+
+__device__ __forceinline__ i32x8 fp4_operand(const u32x4& v) {
+    i32x8 r = {(int)v[0], (int)v[1], (int)v[2], (int)v[3], 0, 0, 0, 0};
+    return r;
+}
+
+#define DUQPP_MFMA(ACC, A, B, SA, SB, SEL) \
+    ACC = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fp4_operand(A), fp4_operand(B), ACC, 4, 4, SEL, (int)(SA), SEL, (int)(SB))
+
+// the eight MFMAs of one quarter step: groups 4 g + SEL of every row tile pair
+#define DUQPP_MFMA8(F, S, SEL)                                    \
+    DUQPP_MFMA(acc[0][0], F.a[0], F.b[0], S.a[0], S.b[0], SEL);   \
+    DUQPP_MFMA(acc[0][1], F.a[0], F.b[1], S.a[0], S.b[1], SEL);   \
+    DUQPP_MFMA(acc[0][2], F.a[0], F.b[2], S.a[0], S.b[2], SEL);   \
+    DUQPP_MFMA(acc[0][3], F.a[0], F.b[3], S.a[0], S.b[3], SEL);   \
+    DUQPP_MFMA(acc[1][0], F.a[1], F.b[0], S.a[1], S.b[0], SEL);   \
+    DUQPP_MFMA(acc[1][1], F.a[1], F.b[1], S.a[1], S.b[1], SEL);   \
+    DUQPP_MFMA(acc[1][2], F.a[1], F.b[2], S.a[1], S.b[2], SEL);   \
+    DUQPP_MFMA(acc[1][3], F.a[1], F.b[3], S.a[1], S.b[3], SEL)
+
+// fragments of quarter Q of the stage whose per-lane base addresses are pa (A tiles) and pb (B tiles)
+template <int Q>
+__device__ __forceinline__ void read_frags(Frags& f, const uint8_t* pa, const uint8_t* pb) {
+    f.a[0] = *(const u32x4*)(pa + Q * 512);
+    f.a[1] = *(const u32x4*)(pa + 4096 + Q * 512);
+    f.b[0] = *(const u32x4*)(pb + Q * 512);
+    f.b[1] = *(const u32x4*)(pb + 4096 + Q * 512);
+    f.b[2] = *(const u32x4*)(pb + 8192 + Q * 512);
+    f.b[3] = *(const u32x4*)(pb + 12288 + Q * 512);
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <bool OUT_BF16>
+__global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 31, g = lane >> 5;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // ---- which output tile: XCD-contiguous renumbering, then groups of kGroupM M-tiles swept
+    // along N, so that the 32 workgroups sharing an L2 cover a compact block of the output
+    const int tiles_m = (p.T + kBM - 1) / kBM, tiles_n = (p.N + kBN - 1) / kBN;
+    int pid;
+    {
+        const int id = blockIdx.x, n = gridDim.x;
+        const int per = n / kNumXCD, rem = n % kNumXCD;
+        const int xcd = id % kNumXCD, slot = id / kNumXCD;
+        pid = xcd * per + (xcd < rem ? xcd : rem) + slot;
+    }
+    const int group_sz = kGroupM * tiles_n;
+    const int first_m = (pid / group_sz) * kGroupM;
+    const int gm = (tiles_m - first_m) < kGroupM ? (tiles_m - first_m) : kGroupM;
+    const int tile_m = first_m + (pid % group_sz) % gm;
+    const int tile_n = (pid % group_sz) / gm;
+
+    const int RTa = (p.T + 31) / 32, RTb = (p.N + 31) / 32;
+    const int NI = p.GP / 8;                               // K steps
+    const int64_t tile_bytes = (int64_t)p.GP * 512;        // codes of one row tile
+    const int64_t tile_sbytes = (int64_t)NI * 256;         // scale words of one row tile
+
+    // ---- LDS-DMA duty of this wave per step: three whole row tiles of codes (12 transfers of 1 KiB)
+    // and one KiB of scale words (the words of four row tiles; wave 3 has only padding to move, which
+    // keeps the number of transfers per wave uniform for the waits below)
+    const uint8_t* dma_src[3];
+    uint32_t dma_dst[3];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) const void*)lds);
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        const int tq = wave * 3 + k;                       // 0..3: A row tiles, 4..11: B row tiles
+        const uint8_t* base;
+        if (tq < kMT) {
+            int rt = tile_m * kMT + tq;
+            if (rt >= RTa) rt = RTa - 1;                   // ragged M: any valid tile, its rows are never stored
+            base = p.a_codes + rt * tile_bytes;
+        } else {
+            int rt = tile_n * kNT + (tq - kMT);
+            if (rt >= RTb) rt = RTb - 1;
+            base = p.b_codes + rt * tile_bytes;
+        }
+        dma_src[k] = base + lane * 16;
+        dma_dst[k] = lds0 + tq * kTileStepBytes;
+    }
+    // scale words: lane l of wave w moves 16 bytes = the words of lanes 4 (l % 16) .. + 3 of row tile
+    // 4 w + l / 16 (tiles 0..3: A, 4..11: B, 12..15: none -- wave 3 re-reads tile 11 into the padding)
+    const uint8_t* sdma_src;
+    {
+        int tq = wave * 4 + (lane >> 4);
+        if (tq > kMT + kNT - 1) tq = kMT + kNT - 1;
+        const uint8_t* base;
+        if (tq < kMT) {
+            int rt = tile_m * kMT + tq;
+            if (rt >= RTa) rt = RTa - 1;
+            base = p.a_scales + rt * tile_sbytes;
+        } else {
+            int rt = tile_n * kNT + (tq - kMT);
+            if (rt >= RTb) rt = RTb - 1;
+            base = p.b_scales + rt * tile_sbytes;
+        }
+        sdma_src = base + (lane & 15) * 16;
+    }
+    const uint32_t sdma_dst = lds0 + kScalesOff + wave * 1024;
+    constexpr int kDmaOps = 13;                            // transfers per wave per step
+    auto issue_dma = [&](int step, int stage) {
+        const uint32_t so = stage * kStageBytes;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) dma_4k(dma_src[k] + (int64_t)step * kTileStepBytes, dma_dst[k] + so);
+        dma_1k(sdma_src + (int64_t)step * 256, sdma_dst + so);
+    };
+
+    // ---- LDS read addresses: lane (r, g) reads group 4 g + i of row r at (4 g + i) * 512 + r * 16;
+    // its scale word of row tile t at kScalesOff + t * 256 + lane * 4
+    const uint8_t* pa0 = lds + g * 2048 + r * 16 + (wm * 2) * kTileStepBytes;
+    const uint8_t* pb0 = lds + g * 2048 + r * 16 + (kMT + wn * 4) * kTileStepBytes;
+    const uint8_t* psa0 = lds + kScalesOff + (wm * 2) * 256 + lane * 4;
+    const uint8_t* psb0 = lds + kScalesOff + (kMT + wn * 4) * 256 + lane * 4;
+    auto read_scales = [&](Scales& s, int stage) {
+        const uint8_t* qa = psa0 + stage * kStageBytes;
+        const uint8_t* qb = psb0 + stage * kStageBytes;
+        s.a[0] = *(const uint32_t*)(qa);
+        s.a[1] = *(const uint32_t*)(qa + 256);
+        s.b[0] = *(const uint32_t*)(qb);
+        s.b[1] = *(const uint32_t*)(qb + 256);
+        s.b[2] = *(const uint32_t*)(qb + 512);
+        s.b[3] = *(const uint32_t*)(qb + 768);
+    };
+
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // ---- prologue: the first two stages.  Transfers complete in issue order, so "at most 13
+    // outstanding" means everything but the newest step's transfers has landed.
+    issue_dma(0, 0);
+    if (NI > 1) {
+        issue_dma(1, 1);
+        wait_vmcnt<kDmaOps>();
+    } else {
+        wait_vmcnt<0>();
+    }
+    workgroup_barrier();
+    Frags f0, f1;
+    Scales sc, sn;
+    read_frags<0>(f0, pa0, pb0);
+    read_scales(sc, 0);
+    sn = sc;
+
+    // One K step.  MORE1 / MORE2: a next step / a step after that exists.
+    auto step = [&](int it, int stage, auto more1_c, auto more2_c) {
+        constexpr bool MORE1 = decltype(more1_c)::value, MORE2 = decltype(more2_c)::value;
+        const int stage1 = stage + 1 == kStages ? 0 : stage + 1;
+        const int stage2 = stage1 + 1 == kStages ? 0 : stage1 + 1;
+        // refill the stage consumed in the previous step (every wave has passed the barrier that
+        // followed its last read of it)
+        if constexpr (MORE2) issue_dma(it + 2, stage2);
+        const uint8_t* pa = pa0 + stage * kStageBytes;
+        const uint8_t* pb = pb0 + stage * kStageBytes;
+        read_frags<1>(f1, pa, pb);
+        DUQPP_MFMA8(f0, sc, 0);
+        read_frags<2>(f0, pa, pb);
+        DUQPP_MFMA8(f1, sc, 1);
+        read_frags<3>(f1, pa, pb);
+        DUQPP_MFMA8(f0, sc, 2);
+        if constexpr (MORE1) {
+            // next stage landed for this wave, then for all; every LDS read of the current stage has
+            // been issued and returns before any later transfer can touch it
+            if constexpr (MORE2) wait_vmcnt<kDmaOps>();
+            else wait_vmcnt<0>();
+            workgroup_barrier();
+            read_frags<0>(f0, pa0 + stage1 * kStageBytes, pb0 + stage1 * kStageBytes);
+            read_scales(sn, stage1);
+        }
+        DUQPP_MFMA8(f1, sc, 3);
+        sc = sn;
+    };
+    int it = 0, stage = 0;
+    for (; it + 2 < NI; ++it) {
+        step(it, stage, std::true_type{}, std::true_type{});
+        stage = stage + 1 == kStages ? 0 : stage + 1;
+    }
+    if (it + 1 < NI) {
+        step(it, stage, std::true_type{}, std::false_type{});
+        stage = stage + 1 == kStages ? 0 : stage + 1;
+        ++it;
+    }
+    step(it, stage, std::false_type{}, std::false_type{});
+
+    // ---- epilogue: acc[i][j][e] of lane (r, g) is row 32 i + 8 (e / 4) + 4 g + e % 4, column 32 j + r
+    const int m0 = tile_m * kBM + wm * 64, n0 = tile_n * kBN + wn * 128;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int col = n0 + 32 * j + r;
+            if (col >= p.N) continue;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = m0 + 32 * i + 8 * (e / 4) + 4 * g + (e % 4);
+                if (row < p.T) {
+                    if (OUT_BF16) ((uint16_t*)p.y)[(int64_t)row * p.ldy + col] = f32_to_bf16_rne(acc[i][j][e]);
+                    else ((float*)p.y)[(int64_t)row * p.ldy + col] = acc[i][j][e];
+                }
+            }
+        }
+}
+
+hipError_t launch_gemm_tiled(const TiledGemmParams& p, hipStream_t stream) {
+    static std::atomic<int> configured{0};
+    if (!configured.load(std::memory_order_acquire)) {
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_tiled_kernel<true>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute((const void*)gemm_tiled_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kGemmLdsBytes);
+        if (e != hipSuccess) return e;
+        configured.store(1, std::memory_order_release);
+    }
+    const int tiles_m = (p.T + kBM - 1) / kBM, tiles_n = (p.N + kBN - 1) / kBN;
+    dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
+    if (p.out_bf16) hipLaunchKernelGGL(gemm_tiled_kernel<true>, grid, block, kGemmLdsBytes, stream, p);
+    else hipLaunchKernelGGL(gemm_tiled_kernel<false>, grid, block, kGemmLdsBytes, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace duqpp

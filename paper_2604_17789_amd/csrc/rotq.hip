@@ -205,7 +205,10 @@ __device__ __forceinline__ void issue_tile_loads(const RotqParams& p, uint8_t* l
     }
 }
 
-template <int WAVES, int STAGES>
+// TILED selects the output placement: row-major through LDS staging, or the tiled operand
+// layout, where a wave's 32 tokens x 16 code bytes of one block are 512 contiguous bytes and
+// go out straight from registers.
+template <int WAVES, int STAGES, bool TILED>
 __global__ __launch_bounds__(WAVES * 64) void rotq_kernel(RotqParams p) {
     using TL = RotqTile<WAVES, STAGES>;
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
@@ -240,24 +243,22 @@ __global__ __launch_bounds__(WAVES * 64) void rotq_kernel(RotqParams p) {
 
     int stage = 0;
     for (int tile = tile0; tile < tile1; ++tile) {
-        // keep P tiles in flight, then wait for this tile only: LDS-DMA loads complete in issue
-        // order and every wave issues exactly 4 per tile, so "at most 4 * (tiles issued after this
-        // one)" outstanding means this tile has landed (stores issued in between only make the
-        // wait stricter).
-        int pre_stage = stage + P;
-        if (pre_stage >= STAGES) pre_stage -= STAGES;
+        // Wait for this tile only: LDS-DMA loads complete in issue order and every wave issues
+        // exactly 4 per tile, so "at most 4 * (tiles issued after this one)" outstanding means this
+        // tile has landed (stores issued in between only make the wait stricter).
         const int ahead = tile1 - 1 - tile;                  // tiles after this one
+        if (P >= 3 && ahead >= 2) wait_vmcnt<8>();
+        else if (P >= 2 && ahead >= 1) wait_vmcnt<4>();
+        else wait_vmcnt<0>();
+        static_assert(P <= 3, "extend the wait ladder for deeper pipelines");
+        __builtin_amdgcn_s_barrier();                        // all waves' pieces of this tile are in LDS,
+                                                             // and every wave is done with the previous tile
+        // refill the stage the previous tile occupied, P tiles ahead
         if (ahead >= P) {
+            int pre_stage = stage + P;
+            if (pre_stage >= STAGES) pre_stage -= STAGES;
             issue_tile_loads<WAVES, STAGES>(p, lds, pre_stage, tile + P, chunk0, wave, lane);
-            wait_vmcnt<4 * P>();
-        } else if (P >= 3 && ahead == 2) {
-            wait_vmcnt<8>();
-        } else if (P >= 2 && ahead == 1) {
-            wait_vmcnt<4>();
-        } else {
-            wait_vmcnt<0>();
         }
-        __builtin_amdgcn_s_barrier();                        // all waves' pieces of this tile are in LDS
 
         const uint32_t in = lds_base + stage * TL::kStageBytes + c * TL::kRowBytes;
         u32x4 x0[2], x1[2];
@@ -272,12 +273,29 @@ __global__ __launch_bounds__(WAVES * 64) void rotq_kernel(RotqParams p) {
         uint32_t byte0 = quantize_group(acc0, o0);
         uint32_t byte1 = quantize_group(acc1, o1);
 
-        // stage the outputs: codes [token][WAVES*2 chunks of 16 B], chunk index swizzled by the token
-        const uint32_t oc = lds_base + TL::kCodesOff + c * TL::kCodeRowBytes + 8 * h;
-        lds_write_b64(oc + (((wave * 2) ^ (c & 15) & (TL::kCodeChunks - 1)) << 4), o0);
-        lds_write_b64(oc + (((wave * 2 + 1) ^ (c & 15) & (TL::kCodeChunks - 1)) << 4), o1);
-        lds_write_b8(lds_base + TL::kScalesOff + c * 16 + wave * 2 + h, h ? byte1 : byte0);
-
+        if constexpr (TILED) {
+            // rows past the end and groups past K are padding of the tiled layout: code 0, scale 127
+            const int jt0 = jb + wave * 2, jt1 = jt0 + 1;
+            const int rt = tile;
+            const bool row_ok = tile * 32 + c < p.rows;
+            if (!row_ok || jt0 >= p.G) { o0 = make_uint2(0, 0); byte0 = 127; }
+            if (!row_ok || jt1 >= p.G) { o1 = make_uint2(0, 0); byte1 = 127; }
+            if (jt0 < p.GP) {                                // GP is even, so jt1 < GP as well
+                uint8_t* ct = p.codes + (((int64_t)rt * p.GP + jt0) * 32 + c) * 16 + 8 * h;
+                *(uint2*)ct = o0;
+                *(uint2*)(ct + 512) = o1;
+                if (h == 0) {
+                    uint8_t* st = p.scales + ((((int64_t)rt * (p.GP / 8) + jt0 / 8) * 2 + (jt0 % 8) / 4) * 32 + c) * 4 + (jt0 % 4);
+                    *(uint16_t*)st = (uint16_t)(byte0 | (byte1 << 8));
+                }
+            }
+        } else {
+            // stage the outputs: codes [token][WAVES*2 chunks of 16 B], chunk index swizzled by the token
+            const uint32_t oc = lds_base + TL::kCodesOff + c * TL::kCodeRowBytes + 8 * h;
+            lds_write_b64(oc + (((wave * 2) ^ (c & 15) & (TL::kCodeChunks - 1)) << 4), o0);
+            lds_write_b64(oc + (((wave * 2 + 1) ^ (c & 15) & (TL::kCodeChunks - 1)) << 4), o1);
+            lds_write_b8(lds_base + TL::kScalesOff + c * 16 + wave * 2 + h, h ? byte1 : byte0);
+        }
         if (p.ydbg) {
             const int row = tile * 32 + c;
             if (row < p.rows) {
@@ -291,33 +309,35 @@ __global__ __launch_bounds__(WAVES * 64) void rotq_kernel(RotqParams p) {
                 }
             }
         }
-        lds_barrier();                                       // outputs of all waves are staged
+        if constexpr (!TILED) {
+            lds_barrier();                                       // outputs of all waves are staged
 
-        // codes: thread i stores 16 bytes; one wave instruction covers 64 / (WAVES*2) full rows
-        {
-            const int r = threadIdx.x / TL::kCodeChunks;     // 0..31
-            const int ch = threadIdx.x % TL::kCodeChunks;
-            const int row = tile * 32 + r;
-            if (row < p.rows && jb + ch < p.G) {
-                u32x4 v = lds_read_b128(lds_base + TL::kCodesOff + r * TL::kCodeRowBytes + ((ch ^ (r & 15) & (TL::kCodeChunks - 1)) << 4));
-                *(u32x4*)(p.codes + ((int64_t)row * p.G + jb + ch) * 16) = v;
+            // codes: thread i stores 16 bytes; one wave instruction covers 64 / (WAVES*2) full rows
+            {
+                const int r = threadIdx.x / TL::kCodeChunks;     // 0..31
+                const int ch = threadIdx.x % TL::kCodeChunks;
+                const int row = tile * 32 + r;
+                if (row < p.rows && jb + ch < p.G) {
+                    u32x4 v = lds_read_b128(lds_base + TL::kCodesOff + r * TL::kCodeRowBytes + ((ch ^ (r & 15) & (TL::kCodeChunks - 1)) << 4));
+                    *(u32x4*)(p.codes + ((int64_t)row * p.G + jb + ch) * 16) = v;
+                }
             }
-        }
-        // scales: one row of the tile per lane of wave 0
-        if (threadIdx.x < 32) {
-            const int row = tile * 32 + threadIdx.x;
-            if (row < p.rows) {
-                const uint32_t sr = lds_base + TL::kScalesOff + threadIdx.x * 16;
-                uint8_t* dst = p.scales + (int64_t)row * p.G + jb;
-                u32x4 v = lds_read_b128(sr);
-                if (jb + TL::kScaleRowBytes <= p.G && (((uintptr_t)dst) & (TL::kScaleRowBytes - 1)) == 0) {
-                    if (TL::kScaleRowBytes == 16) *(u32x4*)dst = v;
-                    else if (TL::kScaleRowBytes == 8) *(uint2*)dst = make_uint2(v[0], v[1]);
-                    else *(uint32_t*)dst = v[0];
-                } else {
+            // scales: one row of the tile per lane of wave 0
+            if (threadIdx.x < 32) {
+                const int row = tile * 32 + threadIdx.x;
+                if (row < p.rows) {
+                    const uint32_t sr = lds_base + TL::kScalesOff + threadIdx.x * 16;
+                    uint8_t* dst = p.scales + (int64_t)row * p.G + jb;
+                    u32x4 v = lds_read_b128(sr);
+                    if (jb + TL::kScaleRowBytes <= p.G && (((uintptr_t)dst) & (TL::kScaleRowBytes - 1)) == 0) {
+                        if (TL::kScaleRowBytes == 16) *(u32x4*)dst = v;
+                        else if (TL::kScaleRowBytes == 8) *(uint2*)dst = make_uint2(v[0], v[1]);
+                        else *(uint32_t*)dst = v[0];
+                    } else {
 #pragma unroll
-                    for (int b = 0; b < TL::kScaleRowBytes; ++b)
-                        if (jb + b < p.G) dst[b] = (uint8_t)(v[b / 4] >> (8 * (b % 4)));
+                        for (int b = 0; b < TL::kScaleRowBytes; ++b)
+                            if (jb + b < p.G) dst[b] = (uint8_t)(v[b / 4] >> (8 * (b % 4)));
+                    }
                 }
             }
         }
@@ -325,11 +345,12 @@ __global__ __launch_bounds__(WAVES * 64) void rotq_kernel(RotqParams p) {
     }
 }
 
-constexpr int kRotqStages = 4;
+constexpr int kRotqStages = 4;             // 3 tiles in flight, one in use
 
 void plan_rotq(RotqParams& p) {
     p.ntiles = (p.rows + 31) / 32;
-    p.nchunks = (p.G + kBlocksPerWG - 1) / kBlocksPerWG;
+    const int cover = p.tiled ? p.GP : p.G;                  // the tiled layout's padding groups are written too
+    p.nchunks = (cover + kBlocksPerWG - 1) / kBlocksPerWG;
     // One resident round: each workgroup keeps its R blocks in registers and walks as many token
     // tiles as the problem allows, so the fetch and split of R is amortised.
     const int64_t slots = (int64_t)kNumCU * kRotqWGPerCU;
@@ -343,14 +364,18 @@ void plan_rotq(RotqParams& p) {
 hipError_t launch_rotq(const RotqParams& p, hipStream_t stream) {
     using TL = RotqTile<kRotqWaves, kRotqStages>;
     static std::atomic<int> configured{0};
-    auto kern = rotq_kernel<kRotqWaves, kRotqStages>;
+    auto kern_rm = rotq_kernel<kRotqWaves, kRotqStages, false>;
+    auto kern_t = rotq_kernel<kRotqWaves, kRotqStages, true>;
     if (!configured.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::kLdsBytes);
+        hipError_t e = hipFuncSetAttribute((const void*)kern_rm, hipFuncAttributeMaxDynamicSharedMemorySize, TL::kLdsBytes);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute((const void*)kern_t, hipFuncAttributeMaxDynamicSharedMemorySize, TL::kLdsBytes);
         if (e != hipSuccess) return e;
         configured.store(1, std::memory_order_release);
     }
     dim3 grid((unsigned)((int64_t)p.nchunks * p.ngroups)), block(kRotqWaves * 64);
-    hipLaunchKernelGGL(kern, grid, block, TL::kLdsBytes, stream, p);
+    if (p.tiled) hipLaunchKernelGGL(kern_t, grid, block, TL::kLdsBytes, stream, p);
+    else hipLaunchKernelGGL(kern_rm, grid, block, TL::kLdsBytes, stream, p);
     return hipGetLastError();
 }
 

@@ -31,3 +31,35 @@ def rel_fro(a, b):
     a = np.asarray(a, dtype=np.float64)
     b = np.asarray(b, dtype=np.float64)
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+# ---- the tiled operand layout, restated in numpy (index arithmetic only) ----
+def tiled_shape(rows, K):
+    G = K // 32
+    return (rows + 31) // 32, (G + 7) // 8 * 8
+
+
+def tile_np(codes, scales):
+    """Row-major [rows, K/2] + [rows, G] -> flat tiled codes [RT][GP][32][16] and scales [RT][GP/8][2][32][4]."""
+    rows, G = scales.shape
+    RT, GP = tiled_shape(rows, G * 32)
+    c = np.zeros((RT * 32, GP, 16), dtype=np.uint8)
+    s = np.full((RT * 32, GP), 127, dtype=np.uint8)
+    c[:rows, :G] = codes.reshape(rows, G, 16)
+    s[:rows, :G] = scales
+    ct = c.reshape(RT, 32, GP, 16).transpose(0, 2, 1, 3)                      # [rt][j][r][16]
+    st = s.reshape(RT, 32, GP // 8, 2, 4).transpose(0, 2, 3, 1, 4)            # [rt][q][g][r][b]
+    return np.ascontiguousarray(ct).reshape(-1), np.ascontiguousarray(st).reshape(-1)
+
+
+def untile_np(codes_t, scales_t, rows, K):
+    """Inverse of tile_np; also returns the padding so that tests can check it."""
+    G = K // 32
+    RT, GP = tiled_shape(rows, K)
+    c = codes_t.reshape(RT, GP, 32, 16).transpose(0, 2, 1, 3).reshape(RT * 32, GP, 16)
+    s = scales_t.reshape(RT, GP // 8, 2, 32, 4).transpose(0, 3, 1, 2, 4).reshape(RT * 32, GP)
+    codes = np.ascontiguousarray(c[:rows, :G]).reshape(rows, G * 16)
+    scales = np.ascontiguousarray(s[:rows, :G])
+    pad_codes = np.concatenate([c[rows:].reshape(-1), c[:rows, G:].reshape(-1)])
+    pad_scales = np.concatenate([s[rows:].reshape(-1), s[:rows, G:].reshape(-1)])
+    return codes, scales, pad_codes, pad_scales

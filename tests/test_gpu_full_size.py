@@ -6,7 +6,7 @@ import pytest
 
 import workloads as wl
 from oracle import linear, mxfp4, rotation
-from helpers import bf16_dev_to_bits, rel_fro, rotation_error_ratio, to_dev, to_dev_bf16
+from helpers import bf16_dev_to_bits, rel_fro, rotation_error_ratio, to_dev, to_dev_bf16, untile_np
 
 pytestmark = pytest.mark.gpu
 
@@ -53,3 +53,24 @@ def test_headline_config_full_size():
     y16_h = bf16_dev_to_bits(y16)
     np.testing.assert_array_equal(y16_h, linear.round_to_bf16_bits(y32_h))
     assert torch.equal(y16, yf)
+
+    # the tiled path, exactly as the bench launches it: same codes in tiled positions, same product
+    print("[full] device: tiled path", flush=True)
+    bct, bst = duqpp.quantize_weights_tiled(w, Rd)
+    act, ast = duqpp.rotate_quantize_tiled(x, Rd)
+    y16_t = duqpp.mxfp4_gemm_tiled(act, ast, bct, bst, T, N, K, out_dtype=1)
+    y32_t = duqpp.mxfp4_gemm_tiled(act, ast, bct, bst, T, N, K, out_dtype=0)
+    yf_t = duqpp.rotq_gemm_tiled(x, Rd, bct, bst, N, out_dtype=1)
+    torch.cuda.synchronize()
+    a_c, a_s, pc, ps = untile_np(act.cpu().numpy(), ast.cpu().numpy(), T, K)
+    np.testing.assert_array_equal(a_c, ac_h)
+    np.testing.assert_array_equal(a_s, as_h)
+    assert np.all(pc == 0) and np.all(ps == 127)
+    b_c, b_s, _, _ = untile_np(bct.cpu().numpy(), bst.cpu().numpy(), N, K)
+    np.testing.assert_array_equal(b_c, bc_h)
+    np.testing.assert_array_equal(b_s, bs_h)
+    y32_th = y32_t.cpu().numpy()
+    assert rel_fro(y32_th[rows], ref_rows) <= 1e-5
+    assert rel_fro(y32_th[:, cols], ref_cols) <= 1e-5
+    np.testing.assert_array_equal(bf16_dev_to_bits(y16_t), linear.round_to_bf16_bits(y32_th))
+    assert torch.equal(y16_t, yf_t)

@@ -1,0 +1,201 @@
+"""GPU parity of the tiled fast path: tile/untile permutations, rotate+quantise with tiled output, and
+the tiled MXFP4 GEMM, all against the CPU oracle (through numpy restatements of the layout's index map)."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import linear, mxfp4, pipeline, rotation
+from helpers import bf16_dev_to_bits, rel_fro, rotation_error_ratio, tile_np, to_dev, to_dev_bf16, untile_np
+
+pytestmark = pytest.mark.gpu
+GEMM_TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+
+    import paper_2604_17789_amd as duqpp
+    assert torch.cuda.is_available()
+    return torch, duqpp
+
+
+def _random_mx(rng, rows, K, lo=118, hi=136):
+    codes = rng.integers(0, 256, size=(rows, K // 2)).astype(np.uint8)
+    scales = rng.integers(lo, hi + 1, size=(rows, K // 32)).astype(np.uint8)
+    return codes, scales
+
+
+def test_numpy_layout_helpers_are_inverse():
+    rng = np.random.default_rng(0)
+    c, s = _random_mx(rng, 45, 32 * 11)
+    ct, st = tile_np(c, s)
+    c2, s2, pc, ps = untile_np(ct, st, 45, 32 * 11)
+    np.testing.assert_array_equal(c, c2)
+    np.testing.assert_array_equal(s, s2)
+    assert np.all(pc == 0) and np.all(ps == 127)
+    # spot-check the documented offsets
+    RT, GP = 2, 16
+    for (row, j, b) in [(0, 0, 0), (33, 10, 7), (44, 5, 15), (31, 3, 2)]:
+        rt, r = divmod(row, 32)
+        assert ct[((rt * GP + j) * 32 + r) * 16 + b] == c[row, j * 16 + b]
+        assert st[(((rt * (GP // 8) + j // 8) * 2 + (j % 8) // 4) * 32 + r) * 4 + j % 4] == s[row, j]
+
+
+@pytest.mark.parametrize("rows,K", [(64, 4096), (45, 352), (1, 32), (300, 1184)])
+def test_tile_and_untile_kernels(env, rows, K):
+    torch, duqpp = env
+    rng = np.random.default_rng(rows + K)
+    c, s = _random_mx(rng, rows, K, 0, 254)
+    ct, st = duqpp.tile_operand(to_dev(c, torch), to_dev(s, torch))
+    torch.cuda.synchronize()
+    ct_ref, st_ref = tile_np(c, s)
+    np.testing.assert_array_equal(ct.cpu().numpy(), ct_ref)
+    np.testing.assert_array_equal(st.cpu().numpy(), st_ref)
+    c2, s2 = duqpp.untile_operand(ct, st, rows, K)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(c2.cpu().numpy(), c)
+    np.testing.assert_array_equal(s2.cpu().numpy(), s)
+
+
+RQ_SHAPES = [(64, 4096), (1, 4096), (16, 14336), (77, 1184), (33, 32), (300, 2048), (256, 14336)]
+
+
+@pytest.mark.parametrize("T,K", RQ_SHAPES)
+def test_rotate_quantize_tiled(env, T, K):
+    """Tiled output = the row-major result (already held to the oracle) in its tiled positions, with
+    code 0 / scale 127 in the padding; checked against the oracle directly as well."""
+    torch, duqpp = env
+    xb = wl.make_activations(f"gpu-rqt-{T}-{K}", T, K, (wl.OutlierSpec(min(8, K // 4), 50.0), wl.OutlierSpec(1, 1000.0, 1)))
+    R = wl.make_rotation_blocks(f"gpu-rqt-{T}-{K}", K // 32)
+    x, Rd = to_dev_bf16(xb, torch), to_dev(R, torch)
+    print(f"[rotq tiled] T={T} K={K}", flush=True)
+    ct, st = duqpp.rotate_quantize_tiled(x, Rd)
+    c_rm, s_rm, yrot = duqpp.rotate_quantize(x, Rd, return_rotated=True)
+    torch.cuda.synchronize()
+    codes, scales, pc, ps = untile_np(ct.cpu().numpy(), st.cpu().numpy(), T, K)
+    assert np.all(pc == 0) and np.all(ps == 127)
+    np.testing.assert_array_equal(codes, c_rm.cpu().numpy())
+    np.testing.assert_array_equal(scales, s_rm.cpu().numpy())
+    c_ref, s_ref = mxfp4.quantize(yrot.cpu().numpy())
+    np.testing.assert_array_equal(codes, c_ref)
+    np.testing.assert_array_equal(scales, s_ref)
+    xf = wl.bf16_bits_to_f32(xb)
+    assert rotation_error_ratio(yrot.cpu().numpy(), rotation.rotate(xf, R), xf) <= 1e-5
+
+
+def test_quantize_weights_tiled(env):
+    torch, duqpp = env
+    N, K = 200, 1184
+    wb = wl.make_weights("gpu-qwt", N, K, 0.02)
+    R = wl.make_rotation_blocks("gpu-qwt", K // 32)
+    ct, st = duqpp.quantize_weights_tiled(to_dev_bf16(wb, torch), to_dev(R, torch))
+    c_rm, s_rm = duqpp.quantize_weights(to_dev_bf16(wb, torch), to_dev(R, torch))
+    torch.cuda.synchronize()
+    codes, scales, pc, ps = untile_np(ct.cpu().numpy(), st.cpu().numpy(), N, K)
+    assert np.all(pc == 0) and np.all(ps == 127)
+    np.testing.assert_array_equal(codes, c_rm.cpu().numpy())
+    np.testing.assert_array_equal(scales, s_rm.cpu().numpy())
+
+
+def _gemm_tiled(env, ac, asc, bc, bsc, out_dtype=0):
+    torch, duqpp = env
+    T, K = ac.shape[0], ac.shape[1] * 2
+    N = bc.shape[0]
+    act, ast = tile_np(ac, asc)
+    bct, bst = tile_np(bc, bsc)
+    y = duqpp.mxfp4_gemm_tiled(to_dev(act, torch), to_dev(ast, torch), to_dev(bct, torch), to_dev(bst, torch),
+                               T, N, K, out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    return y
+
+
+GEMM_SHAPES = [
+    (64, 96, 512),
+    (77, 130, 1184),      # ragged in T, N; 37 groups padded to 40
+    (1, 257, 4096),       # decode
+    (16, 300, 2048),
+    (130, 70, 32),        # a single group (one K step of mostly padding)
+    (200, 264, 2304),
+    (129, 513, 1312),
+    (256, 512, 256),      # exactly one K step
+    (384, 768, 512),      # two K steps, several workgroups
+    (300, 1000, 768),     # three K steps
+]
+
+
+@pytest.mark.parametrize("T,N,K", GEMM_SHAPES)
+def test_gemm_tiled_random_codes(env, T, N, K):
+    rng = np.random.default_rng(T * 1000003 + N * 1009 + K)
+    ac, asc = _random_mx(rng, T, K)
+    bc, bsc = _random_mx(rng, N, K)
+    print(f"[gemm tiled] random codes T={T} N={N} K={K}", flush=True)
+    y = _gemm_tiled(env, ac, asc, bc, bsc).cpu().numpy()
+    ref = linear.mxfp4_gemm(ac, asc, bc, bsc)
+    assert rel_fro(y, ref) <= GEMM_TOL
+
+
+def test_gemm_tiled_exact_integer_case(env):
+    rng = np.random.default_rng(78)
+    T, N, K = 160, 320, 14336
+    ac = rng.integers(0, 256, size=(T, K // 2)).astype(np.uint8)
+    bc = rng.integers(0, 256, size=(N, K // 2)).astype(np.uint8)
+    asc = np.full((T, K // 32), 125, dtype=np.uint8)
+    bsc = np.full((N, K // 32), 131, dtype=np.uint8)
+    y = _gemm_tiled(env, ac, asc, bc, bsc).cpu().numpy()
+    ref = linear.mxfp4_gemm(ac, asc, bc, bsc)
+    np.testing.assert_array_equal(y, ref.astype(np.float32))
+
+
+def test_gemm_tiled_scale_bytes_pair_with_their_own_group(env):
+    T, N, K = 70, 300, 1024
+    G = K // 32
+    rng = np.random.default_rng(6)
+    ac = np.zeros((T, K // 2), dtype=np.uint8)
+    bc = np.zeros((N, K // 2), dtype=np.uint8)
+    pos = rng.integers(0, 32, size=G)
+    for j in range(G):
+        k = 32 * j + int(pos[j])
+        ac[:, k // 2] = 0x02 << (4 * (k & 1))
+        bc[:, k // 2] = 0x02 << (4 * (k & 1))
+    asc = (110 + (np.arange(T)[:, None] * 7 + np.arange(G)[None, :] * 3) % 9).astype(np.uint8)
+    bsc = (120 + (np.arange(N)[:, None] * 5 + np.arange(G)[None, :]) % 8).astype(np.uint8)
+    y = _gemm_tiled(env, ac, asc, bc, bsc).cpu().numpy()
+    ref = linear.mxfp4_gemm(ac, asc, bc, bsc)
+    np.testing.assert_array_equal(y, ref.astype(np.float32))   # sums of at most 32 powers of two within 2^17: exact
+
+
+def test_gemm_tiled_bf16_output(env):
+    rng = np.random.default_rng(14)
+    T, N, K = 70, 200, 1024
+    ac, asc = _random_mx(rng, T, K)
+    bc, bsc = _random_mx(rng, N, K)
+    y32 = _gemm_tiled(env, ac, asc, bc, bsc, 0).cpu().numpy()
+    y16 = bf16_dev_to_bits(_gemm_tiled(env, ac, asc, bc, bsc, 1))
+    np.testing.assert_array_equal(y16, linear.round_to_bf16_bits(y32))
+    ref16 = linear.round_to_bf16_bits(linear.mxfp4_gemm(ac, asc, bc, bsc).astype(np.float32))
+    assert np.max(np.abs(y16.astype(np.int32) - ref16.astype(np.int32))) <= 1
+
+
+@pytest.mark.parametrize("T,N,K", [(1, 512, 4096), (16, 4096, 1184), (100, 200, 1024), (64, 4096, 4096)])
+def test_whole_tiled_path_and_fused_call(env, T, N, K):
+    torch, duqpp = env
+    xb = wl.make_activations(f"tiled-{T}", T, K, (wl.OutlierSpec(8, 50.0),))
+    wb = wl.make_weights(f"tiled-{T}", N, K, 0.02)
+    R = wl.make_rotation_blocks(f"tiled-{T}", K // 32)
+    x, w, Rd = to_dev_bf16(xb, torch), to_dev_bf16(wb, torch), to_dev(R, torch)
+    bct, bst = duqpp.quantize_weights_tiled(w, Rd)
+    act, ast = duqpp.rotate_quantize_tiled(x, Rd)
+    for dt in (0, 1):
+        y = duqpp.mxfp4_gemm_tiled(act, ast, bct, bst, T, N, K, out_dtype=dt)
+        yf = duqpp.rotq_gemm_tiled(x, Rd, bct, bst, N, out_dtype=dt)
+        torch.cuda.synchronize()
+        assert torch.equal(y, yf)
+    ac, asc, _, _ = untile_np(act.cpu().numpy(), ast.cpu().numpy(), T, K)
+    bc, bsc, _, _ = untile_np(bct.cpu().numpy(), bst.cpu().numpy(), N, K)
+    ref = linear.mxfp4_gemm(ac, asc, bc, bsc)
+    y32 = duqpp.mxfp4_gemm_tiled(act, ast, bct, bst, T, N, K).cpu().numpy()
+    assert rel_fro(y32, ref) <= GEMM_TOL
+    # and the row-major entry points give the same product from the same codes
+    y_rm = duqpp.mxfp4_gemm(to_dev(ac, torch), to_dev(asc, torch), to_dev(bc, torch), to_dev(bsc, torch)).cpu().numpy()
+    assert rel_fro(y_rm, ref) <= GEMM_TOL
