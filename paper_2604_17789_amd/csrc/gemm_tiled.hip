@@ -73,6 +73,18 @@ __device__ __forceinline__ void dma_4k(const uint8_t* src_lane, uint32_t lds_dst
         : "memory", "m0");
 }
 
+// One KiB-sized transfer with a compile-time offset applied to both addresses.
+template <int OFF>
+__device__ __forceinline__ void dma_1k_at(const uint8_t* src_lane, uint32_t lds_dst) {
+    asm volatile(
+        "s_mov_b32 m0, %1\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %0, off offset:%2"
+        :
+        : "v"(src_lane), "s"(lds_dst), "n"(OFF)
+        : "memory", "m0");
+}
+
 __device__ __forceinline__ void dma_1k(const uint8_t* src_lane, uint32_t lds_dst) {
     asm volatile(
         "s_mov_b32 m0, %1\n\t"
@@ -252,17 +264,55 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
         constexpr bool MORE1 = decltype(more1_c)::value, MORE2 = decltype(more2_c)::value;
         const int stage1 = stage + 1 == kStages ? 0 : stage + 1;
         const int stage2 = stage1 + 1 == kStages ? 0 : stage1 + 1;
-        // refill the stage consumed in the previous step (every wave has passed the barrier that
-        // followed its last read of it)
-        if constexpr (MORE2) issue_dma(it + 2, stage2);
+        // The 13 transfers that refill the stage consumed in the previous step (every wave has passed
+        // the barrier that followed its last read of it) are spread over the first three quarters, one
+        // every other MFMA: the CU's one texture path moves 64 B/clk, i.e. a step's 52 KiB take 832 of
+        // the step's 1024 MFMA cycles, and a wave that issues its transfers in a burst sits behind the
+        // other waves' bursts with its MFMAs waiting.
+        const uint8_t* d0 = dma_src[0] + (int64_t)(it + 2) * kTileStepBytes;
+        const uint8_t* d1 = dma_src[1] + (int64_t)(it + 2) * kTileStepBytes;
+        const uint8_t* d2 = dma_src[2] + (int64_t)(it + 2) * kTileStepBytes;
+        const uint8_t* d3 = sdma_src + (int64_t)(it + 2) * 256;
+        const uint32_t so2 = stage2 * kStageBytes;
+        auto dma_slot = [&](auto kc) {
+            constexpr int k = decltype(kc)::value;
+            if constexpr (MORE2) {
+                if constexpr (k < 4) dma_1k_at<(k % 4) * 1024>(d0, dma_dst[0] + so2);
+                else if constexpr (k < 8) dma_1k_at<(k % 4) * 1024>(d1, dma_dst[1] + so2);
+                else if constexpr (k < 12) dma_1k_at<(k % 4) * 1024>(d2, dma_dst[2] + so2);
+                else dma_1k_at<0>(d3, sdma_dst + so2);
+            }
+        };
         const uint8_t* pa = pa0 + stage * kStageBytes;
         const uint8_t* pb = pb0 + stage * kStageBytes;
-        read_frags<1>(f1, pa, pb);
-        DUQPP_MFMA8(f0, sc, 0);
-        read_frags<2>(f0, pa, pb);
-        DUQPP_MFMA8(f1, sc, 1);
-        read_frags<3>(f1, pa, pb);
-        DUQPP_MFMA8(f0, sc, 2);
+#define DUQPP_PIN __builtin_amdgcn_sched_barrier(0)
+#define DUQPP_DMA(K) dma_slot(std::integral_constant<int, K>{}); DUQPP_PIN
+        // quarter Q (fragments CUR) while the fragments of quarter Q + 1 (NXT) are read; D0..D3: transfers
+#define DUQPP_QUARTER(Q, CUR, NXT, D0, D1, D2, D3)                                            \
+        DUQPP_DMA(D0);                                                                         \
+        NXT.a[0] = *(const u32x4*)(pa + (Q + 1) * 512);                                         \
+        DUQPP_MFMA(acc[0][0], CUR.a[0], CUR.b[0], sc.a[0], sc.b[0], Q); DUQPP_PIN;              \
+        NXT.b[0] = *(const u32x4*)(pb + (Q + 1) * 512);                                         \
+        DUQPP_MFMA(acc[0][1], CUR.a[0], CUR.b[1], sc.a[0], sc.b[1], Q); DUQPP_PIN;              \
+        DUQPP_DMA(D1);                                                                         \
+        NXT.b[1] = *(const u32x4*)(pb + 4096 + (Q + 1) * 512);                                  \
+        DUQPP_MFMA(acc[0][2], CUR.a[0], CUR.b[2], sc.a[0], sc.b[2], Q); DUQPP_PIN;              \
+        NXT.b[2] = *(const u32x4*)(pb + 8192 + (Q + 1) * 512);                                  \
+        DUQPP_MFMA(acc[0][3], CUR.a[0], CUR.b[3], sc.a[0], sc.b[3], Q); DUQPP_PIN;              \
+        DUQPP_DMA(D2);                                                                         \
+        NXT.b[3] = *(const u32x4*)(pb + 12288 + (Q + 1) * 512);                                 \
+        DUQPP_MFMA(acc[1][0], CUR.a[1], CUR.b[0], sc.a[1], sc.b[0], Q); DUQPP_PIN;              \
+        NXT.a[1] = *(const u32x4*)(pa + 4096 + (Q + 1) * 512);                                  \
+        DUQPP_MFMA(acc[1][1], CUR.a[1], CUR.b[1], sc.a[1], sc.b[1], Q); DUQPP_PIN;              \
+        DUQPP_DMA(D3);                                                                         \
+        DUQPP_MFMA(acc[1][2], CUR.a[1], CUR.b[2], sc.a[1], sc.b[2], Q);                         \
+        DUQPP_MFMA(acc[1][3], CUR.a[1], CUR.b[3], sc.a[1], sc.b[3], Q); DUQPP_PIN
+        DUQPP_DMA(12);
+        DUQPP_QUARTER(0, f0, f1, 0, 1, 2, 3);
+        DUQPP_QUARTER(1, f1, f0, 4, 5, 6, 7);
+        DUQPP_QUARTER(2, f0, f1, 8, 9, 10, 11);
+#undef DUQPP_QUARTER
+#undef DUQPP_DMA
         if constexpr (MORE1) {
             // next stage landed for this wave, then for all; every LDS read of the current stage has
             // been issued and returns before any later transfer can touch it
@@ -273,6 +323,16 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
             read_scales(sn, stage1);
         }
         DUQPP_MFMA8(f1, sc, 3);
+        if constexpr (MORE1) {
+            // the reads above (6 fragments, 3 paired scale reads) two at a time ahead of the MFMAs
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            }
+        }
+        DUQPP_PIN;
+#undef DUQPP_PIN
         sc = sn;
     };
     int it = 0, stage = 0;
