@@ -349,6 +349,43 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
 
     // ---- epilogue: acc[i][j][e] of lane (r, g) is row 32 i + 8 (e / 4) + 4 g + e % 4, column 32 j + r
     const int m0 = tile_m * kBM + wm * 64, n0 = tile_n * kBN + wn * 128;
+    if constexpr (OUT_BF16) {
+        // A direct store would write 2 bytes per lane, 64 contiguous bytes per instruction and row.
+        // Instead the wave's 64 x 128 tile is transposed through LDS (free once every wave is past the
+        // K loop) and leaves as 16-byte pieces, 256 contiguous bytes per row.  Rows are padded to 272
+        // bytes so that the two half-waves (four rows apart) fall on different banks.
+        const bool vec_ok = ((reinterpret_cast<uintptr_t>(p.y) & 15) == 0) && (p.ldy % 8) == 0;
+        if (vec_ok) {
+            constexpr int kRowPitch = 272;
+            workgroup_barrier();                           // all waves have read their last fragments
+            uint8_t* ep = lds + wave * (64 * kRowPitch);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int row = 32 * i + 8 * (e / 4) + 4 * g + (e % 4);
+                        *(uint16_t*)(ep + row * kRowPitch + (32 * j + r) * 2) = f32_to_bf16_rne(acc[i][j][e]);
+                    }
+            // same wave wrote and reads: program order suffices within a wave
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                const int row = k * 4 + (lane >> 4), ch = lane & 15;
+                const int grow = m0 + row, gcol = n0 + ch * 8;
+                if (grow < p.T && gcol < p.N) {
+                    const u32x4 v = *(const u32x4*)(ep + row * kRowPitch + ch * 16);
+                    uint16_t* dst = (uint16_t*)p.y + (int64_t)grow * p.ldy + gcol;
+                    if (gcol + 8 <= p.N) {
+                        *(u32x4*)dst = v;
+                    } else {                               // ragged right edge
+                        for (int c = 0; c < 8 && gcol + c < p.N; ++c) dst[c] = (uint16_t)(v[c / 2] >> (16 * (c & 1)));
+                    }
+                }
+            }
+            return;
+        }
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
