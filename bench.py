@@ -22,8 +22,10 @@ METRIC = "rotate+MXFP4-quant GB/s (%HBM peak); W4A4 MXFP4 GEMM TFLOPS (%MFMA pea
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
 FP4_PEAK_TFLOPS = 10100.0     # MI355X dense MXFP4 matrix peak, published (256 CU x 2.4 GHz x 16384 flop/clk/CU)
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None until measured.
-MEASURED_TRAFFIC = {"gemm": None, "rotq": None}
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE (x 2.000) + WRITE_SIZE (x 1.000), the factors a plain
+# 256 MiB device copy gives for the same counters; workload c2_8b_down_prefill
+# (profiles/gemm_tiled_and_rotq_c2_8b_down_prefill_hbm_traffic.md).
+MEASURED_TRAFFIC = {"gemm": 156.26e6 + 16.78e6, "rotq": 60.92e6 + 15.60e6}
 
 
 def rotq_algorithmic_bytes(T, K):
@@ -39,6 +41,9 @@ def main():
     ap.add_argument("--config", default="c2_8b_down_prefill")
     ap.add_argument("--sets", type=int, default=8, help="distinct buffer sets the batches rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="instead of the workload, run a plain device copy of known size (256 MiB, 20 times): "
+                         "the reference against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards by tokens or output channels "
@@ -54,6 +59,16 @@ def main():
     assert torch.cuda.is_available(), "no GPU visible"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.copy_calibration:
+        nbytes = 256 << 20
+        srcs = [torch.full((nbytes // 4,), float(i), dtype=torch.float32, device=dev) for i in range(4)]
+        dsts = [torch.empty_like(t) for t in srcs]
+        for i in range(20):
+            dsts[i % 4].copy_(srcs[i % 4])
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read_per_launch": nbytes, "bytes_written_per_launch": nbytes,
+                                               "launches": 20}}))
+        return
     cfg = wl.CONFIGS[args.config]
     T, K, N = cfg["T"], cfg["K"], cfg["N"]
     out_dtype = duqpp.binding.BF16 if cfg["out"] == "bf16" else duqpp.binding.F32
@@ -151,11 +166,12 @@ def main():
         },
         "roofline": {"kernel": "mxfp4_gemm", "bound": "mfma", "achieved": round(gemm_tflops, 1),
                      "peak": FP4_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(gemm_tflops / FP4_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC["gemm"]},
+                     "frac": round(gemm_tflops / FP4_PEAK_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC["gemm"] if args.config == "c2_8b_down_prefill" else None},
         "roofline_rotate_quantize": {"kernel": "rotq", "bound": "hbm", "achieved": round(rotq_gbps, 1),
                                      "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                      "frac": round(rotq_gbps / HBM_PEAK_GBPS, 4),
-                                     "traffic": MEASURED_TRAFFIC["rotq"]},
+                                     "traffic": MEASURED_TRAFFIC["rotq"] if args.config == "c2_8b_down_prefill" else None},
     }
 
     # ---- the CPU oracle on a bounded sample of the same workload ---------------------------
