@@ -80,6 +80,7 @@ struct TiledGemmParams {
     int T, N, GP;
     void* y; int64_t ldy; int out_bf16;
 };
-hipError_t launch_gemm_tiled(const TiledGemmParams& p, hipStream_t stream);
+hipError_t launch_gemm_tiled(const TiledGemmParams& p, hipStream_t stream);     // picks the kernel by shape
+hipError_t launch_gemm_decode(const TiledGemmParams& p, hipStream_t stream);    // T <= 32
 
 }  // namespace duqpp

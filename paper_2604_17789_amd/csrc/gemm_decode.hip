@@ -1,0 +1,114 @@
+// Decode-shape W4A4 MXFP4 GEMM (Eq. 5 with a handful of tokens): T <= 32, so the activations are a
+// single row tile and the product is bound by streaming the weights once from HBM (N * K * 17/32
+// bytes).  Tiled operand layout, same instruction and K permutation as the prefill kernel.
+//
+// One workgroup of 8 waves per weight row tile (32 output channels).  The waves split K: each owns a
+// contiguous range of K steps, loads its weight fragments straight from global memory into registers
+// (512 contiguous bytes per half-wave and load, every byte read once chip-wide), its activation
+// fragments from the L2-resident activation tile, and accumulates one 32 x 32 tile.  The eight
+// partial tiles are then summed through LDS in a fixed order (deterministic) and the first T rows
+// are stored.
+#include "duqpp_internal.h"
+
+namespace duqpp {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kDecWaves = 8;
+
+__device__ __forceinline__ i32x8 dec_fp4_operand(const u32x4& v) {
+    i32x8 r = {(int)v[0], (int)v[1], (int)v[2], (int)v[3], 0, 0, 0, 0};
+    return r;
+}
+
+#define DUQPP_DEC_MFMA(ACC, A, B, SA, SB, SEL) \
+    ACC = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(dec_fp4_operand(A), dec_fp4_operand(B), ACC, 4, 4, SEL, (int)(SA), SEL, (int)(SB))
+
+struct DecStep {
+    u32x4 a[4], b[4];
+    uint32_t sa, sb;
+};
+
+__device__ __forceinline__ void dec_load(DecStep& d, const uint8_t* a_codes, const uint8_t* a_scales,
+                                         const uint8_t* b_codes, const uint8_t* b_scales, int step, int lane_code,
+                                         int lane4) {
+    const uint8_t* pa = a_codes + (int64_t)step * 4096 + lane_code;
+    const uint8_t* pb = b_codes + (int64_t)step * 4096 + lane_code;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        d.a[i] = *(const u32x4*)(pa + i * 512);
+        d.b[i] = __builtin_nontemporal_load((const u32x4*)(pb + i * 512));   // weights are read once
+    }
+    d.sa = *(const uint32_t*)(a_scales + (int64_t)step * 256 + lane4);
+    d.sb = *(const uint32_t*)(b_scales + (int64_t)step * 256 + lane4);
+}
+
+__device__ __forceinline__ uint16_t dec_f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <bool OUT_BF16>
+__global__ __launch_bounds__(kDecWaves * 64) void gemm_decode_kernel(TiledGemmParams p) {
+    __shared__ float part[kDecWaves][16][64];              // [wave][accumulator register][lane]
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int r = lane & 31, g = lane >> 5;
+    const int rt = blockIdx.x;                             // weight row tile
+    const int NI = p.GP / 8;
+    const int per = (NI + kDecWaves - 1) / kDecWaves;
+    const int s0 = wave * per;
+    int s1 = s0 + per;
+    if (s1 > NI) s1 = NI;
+
+    const uint8_t* b_codes = p.b_codes + (int64_t)rt * p.GP * 512;
+    const uint8_t* b_scales = p.b_scales + (int64_t)rt * NI * 256;
+    const int lane_code = g * 2048 + r * 16;               // group 4 g + i of row r sits at (4 g + i) * 512 + r * 16
+    const int lane4 = lane * 4;
+
+    f32x16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+
+    // two steps in flight per wave: the loads of step s + 1 are issued before the MFMAs of step s
+    DecStep cur, nxt;
+    if (s0 < s1) dec_load(cur, p.a_codes, p.a_scales, b_codes, b_scales, s0, lane_code, lane4);
+    for (int s = s0; s < s1; ++s) {
+        if (s + 1 < s1) dec_load(nxt, p.a_codes, p.a_scales, b_codes, b_scales, s + 1, lane_code, lane4);
+        DUQPP_DEC_MFMA(acc, cur.a[0], cur.b[0], cur.sa, cur.sb, 0);
+        DUQPP_DEC_MFMA(acc, cur.a[1], cur.b[1], cur.sa, cur.sb, 1);
+        DUQPP_DEC_MFMA(acc, cur.a[2], cur.b[2], cur.sa, cur.sb, 2);
+        DUQPP_DEC_MFMA(acc, cur.a[3], cur.b[3], cur.sa, cur.sb, 3);
+        cur = nxt;
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) part[wave][e][lane] = acc[e];
+    __syncthreads();
+    // acc[e] of lane (r, g): token 8 (e / 4) + 4 g + e % 4, output channel 32 rt + r.
+    // 1024 outputs, 512 threads: thread t sums register e = t / 64 and e + 8 of lane t % 64 over the waves.
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int e = (threadIdx.x >> 6) + 8 * h;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < kDecWaves; ++w) sum += part[w][e][lane];
+        const int tok = 8 * (e / 4) + 4 * g + (e % 4);
+        const int col = rt * 32 + r;
+        if (tok < p.T && col < p.N) {
+            if (OUT_BF16) ((uint16_t*)p.y)[(int64_t)tok * p.ldy + col] = dec_f32_to_bf16_rne(sum);
+            else ((float*)p.y)[(int64_t)tok * p.ldy + col] = sum;
+        }
+    }
+}
+
+hipError_t launch_gemm_decode(const TiledGemmParams& p, hipStream_t stream) {
+    dim3 grid((unsigned)((p.N + 31) / 32)), block(kDecWaves * 64);
+    if (p.out_bf16) hipLaunchKernelGGL(gemm_decode_kernel<true>, grid, block, 0, stream, p);
+    else hipLaunchKernelGGL(gemm_decode_kernel<false>, grid, block, 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace duqpp

@@ -115,6 +115,8 @@ GEMM_SHAPES = [
     (77, 130, 1184),      # ragged in T, N; 37 groups padded to 40
     (1, 257, 4096),       # decode
     (16, 300, 2048),
+    (24, 200, 1184),      # one ragged row tile, ragged K steps over the decode kernel's eight waves
+    (32, 96, 32),         # decode kernel, a single group
     (130, 70, 32),        # a single group (one K step of mostly padding)
     (200, 264, 2304),
     (129, 513, 1312),
@@ -199,3 +201,28 @@ def test_whole_tiled_path_and_fused_call(env, T, N, K):
     # and the row-major entry points give the same product from the same codes
     y_rm = duqpp.mxfp4_gemm(to_dev(ac, torch), to_dev(asc, torch), to_dev(bc, torch), to_dev(bsc, torch)).cpu().numpy()
     assert rel_fro(y_rm, ref) <= GEMM_TOL
+
+
+@pytest.mark.parametrize("name", ["c3_decode_gateup_T1", "c3_decode_gateup_T16", "c3_decode_down_T4", "c3_decode_down_T16"])
+def test_decode_configs(env, name):
+    """LLaMA-3-8B decode shapes: weights resident as tiled MXFP4, activations rotated + quantised per call."""
+    torch, duqpp = env
+    cfg = wl.CONFIGS[name]
+    T, K, N = cfg["T"], cfg["K"], cfg["N"]
+    xb = wl.make_activations(name, T, K, cfg["outliers"])
+    wb = wl.make_weights(name, N, K, cfg["w_std"])
+    R = wl.make_rotation_blocks(name, K // 32)
+    x, w, Rd = to_dev_bf16(xb, torch), to_dev_bf16(wb, torch), to_dev(R, torch)
+    print(f"[decode] {name} T={T} K={K} N={N}", flush=True)
+    bct, bst = duqpp.quantize_weights_tiled(w, Rd)
+    act, ast = duqpp.rotate_quantize_tiled(x, Rd)
+    y = duqpp.mxfp4_gemm_tiled(act, ast, bct, bst, T, N, K)
+    yf = duqpp.rotq_gemm_tiled(x, Rd, bct, bst, N)
+    torch.cuda.synchronize()
+    assert torch.equal(y, yf)
+    ac, asc, _, _ = untile_np(act.cpu().numpy(), ast.cpu().numpy(), T, K)
+    bc, bsc, _, _ = untile_np(bct.cpu().numpy(), bst.cpu().numpy(), N, K)
+    c_ref, s_ref, _ = pipeline.rotate_quantize(xb, R)      # activation codes: own rotations may differ in rare ties
+    assert np.mean(mxfp4.unpack_codes(ac) != mxfp4.unpack_codes(c_ref)) < 1e-3
+    ref = linear.mxfp4_gemm(ac, asc, bc, bsc)
+    assert rel_fro(y.cpu().numpy(), ref) <= GEMM_TOL
