@@ -3,8 +3,10 @@
 
 A step is one pass of the whole path over one batch: rotate + MXFP4-quantise the activations
 (duqpp_rotate_quantize) and multiply them with the pre-rotated MXFP4 weights (duqpp_mxfp4_gemm).
-The workload is LLaMA-3-8B down_proj prefill (T=2048, K=14336, N=4096, bf16 output) with seeded
+The default workload is LLaMA-3-8B down_proj prefill (T=2048, K=14336, N=4096, bf16 output) with seeded
 synthetic inputs carrying injected outlier channels; the weights are prepared once, before timing.
+--config selects the other single-layer shapes or the seven-linear decoder-layer set (one step = every
+linear of the set once).
 Batches rotate through several buffer sets so that inputs come from HBM rather than from the
 256 MB last-level cache.  Prints one JSON line.
 """
@@ -41,6 +43,7 @@ def main():
     ap.add_argument("--config", default="c2_8b_down_prefill")
     ap.add_argument("--sets", type=int, default=8, help="distinct buffer sets the batches rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eager", action="store_true", help="time eager launches only (no HIP graph capture)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the workload, run a plain device copy of known size (256 MiB, 20 times): "
                          "the reference against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -69,10 +72,20 @@ def main():
         print(json.dumps({"copy_calibration": {"bytes_read_per_launch": nbytes, "bytes_written_per_launch": nbytes,
                                                "launches": 20}}))
         return
-    cfg = wl.CONFIGS[args.config]
-    T, K, N = cfg["T"], cfg["K"], cfg["N"]
+    # A workload is a list of linears (name, K, N, outliers) run over the same T tokens: one for the single-layer
+    # configurations, seven for the decoder-layer set.
+    if args.config in wl.LAYER_SET_CONFIGS:
+        cfg = wl.LAYER_SET_CONFIGS[args.config]
+        linears = [(nm, k, n, cfg["outliers"] if has else ()) for nm, k, n, has in cfg["layers"]]
+        if args.sets == 8:
+            args.sets = 2                                   # 1.3 GB of activations per set: two already exceed the cache
+    else:
+        cfg = wl.CONFIGS[args.config]
+        linears = [("linear", cfg["K"], cfg["N"], cfg["outliers"])]
+    T = cfg["T"]
     out_dtype = duqpp.binding.BF16 if cfg["out"] == "bf16" else duqpp.binding.F32
-    G = K // 32
+    single = len(linears) == 1
+    K, N = linears[-1][1], linears[-1][2]                   # the linear the oracle sample is taken from
 
     def dev_bf16(bits):
         return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
@@ -81,93 +94,109 @@ def main():
     nsets = max(1, args.sets)
     sets = []
     x0_bits = None
-    w0_bits = None
     R0 = None
     for s in range(nsets):
-        xb = wl.make_activations(f"bench-{args.config}-{s}", T, K, cfg["outliers"])
-        wb = wl.make_weights(f"bench-{args.config}-{s}", N, K, cfg["w_std"])
-        R = wl.make_rotation_blocks(f"bench-{args.config}-{s}", G)
-        if s == 0:
-            x0_bits, w0_bits, R0 = xb, wb, R
-        x, Rd = dev_bf16(xb), torch.from_numpy(R).to(dev)
-        w = dev_bf16(wb)
-        bc, bs = duqpp.quantize_weights_tiled(w, Rd)      # offline weight transform (tiled layout), not timed
-        del w
-        cb, sb = duqpp.tiled_bytes(T, K)
-        sets.append(dict(
-            x=x, R=Rd, bc=bc, bs=bs,
-            ac=torch.empty(cb, dtype=torch.uint8, device=dev),
-            asc=torch.empty(sb, dtype=torch.uint8, device=dev),
-            y=torch.empty((T, N), dtype=torch.bfloat16 if cfg["out"] == "bf16" else torch.float32, device=dev)))
+        layers = []
+        for nm, k, n, outl in linears:
+            tag = f"bench-{args.config}-{s}" if single else f"bench-{args.config}-{nm}-{s}"
+            xb = wl.make_activations(tag, T, k, outl)
+            wb = wl.make_weights(tag, n, k, cfg["w_std"])
+            R = wl.make_rotation_blocks(tag, k // 32)
+            if s == 0 and nm == linears[-1][0]:
+                x0_bits, R0 = xb, R
+            x, Rd = dev_bf16(xb), torch.from_numpy(R).to(dev)
+            w = dev_bf16(wb)
+            bc, bs = duqpp.quantize_weights_tiled(w, Rd)  # offline weight transform (tiled layout), not timed
+            del w, wb, xb
+            cb, sb = duqpp.tiled_bytes(T, k)
+            layers.append(dict(
+                name=nm, K=k, N=n, x=x, R=Rd, bc=bc, bs=bs,
+                ac=torch.empty(cb, dtype=torch.uint8, device=dev),
+                asc=torch.empty(sb, dtype=torch.uint8, device=dev),
+                y=torch.empty((T, n), dtype=torch.bfloat16 if cfg["out"] == "bf16" else torch.float32, device=dev)))
+        sets.append(layers)
     torch.cuda.synchronize()
 
     # the timed path: activations rotated + quantised into the tiled operand layout, then the tiled GEMM
+    def rotq1(l):
+        duqpp.rotate_quantize_tiled(l["x"], l["R"], out=(l["ac"], l["asc"]))
+
+    def gemm1(l):
+        duqpp.mxfp4_gemm_tiled(l["ac"], l["asc"], l["bc"], l["bs"], T, l["N"], l["K"], out_dtype=out_dtype, out=l["y"])
+
     def rotq(s):
-        duqpp.rotate_quantize_tiled(s["x"], s["R"], out=(s["ac"], s["asc"]))
+        for l in s:
+            rotq1(l)
 
     def gemm(s):
-        duqpp.mxfp4_gemm_tiled(s["ac"], s["asc"], s["bc"], s["bs"], T, N, K, out_dtype=out_dtype, out=s["y"])
+        for l in s:
+            gemm1(l)
 
-    def step(i):
-        s = sets[i % nsets]
-        rotq(s)
-        gemm(s)
+    def step(s):
+        for l in s:
+            rotq1(l)
+            gemm1(l)
 
-    # ---- whole-step timing ---------------------------------------------------------------
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-
-    # ---- per-kernel timing with events on the launch stream -------------------------------
-    # The launches are captured once into a HIP graph and replayed, so that the GPU runs them back to
-    # back: issued one by one from Python, launches of a ~10 us kernel measure the interpreter, not the
-    # kernel.  (The kernels record no memset nodes.)  The eager figure is kept beside it.
-    def time_kernel(fn):
+    # ---- timing ---------------------------------------------------------------------------
+    # `fn` is run args.steps times over the rotating buffer sets, bracketed by device synchronisation.  The
+    # launches are captured once into a HIP graph and the graph is replayed, so that the GPU runs them back to
+    # back: issued one by one from Python, launches of a ~10 us kernel measure the interpreter, not the kernel.
+    # (The kernels record no memset nodes.)  The figure from eager launches is kept beside it.  Events are
+    # recorded on the stream the kernels are launched on.
+    def time_region(fn, eager_only=False):
         for i in range(min(args.warmup, 10)):
             fn(sets[i % nsets])
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
+        t0 = time.perf_counter()
         e0.record()
         for i in range(args.steps):
             fn(sets[i % nsets])
         e1.record()
-        e1.synchronize()
+        torch.cuda.synchronize()
+        eager_wall_us = (time.perf_counter() - t0) * 1e6 / args.steps
         eager_us = e0.elapsed_time(e1) * 1e3 / args.steps
-        graph_us = None
-        try:
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.stream(side):
-                with torch.cuda.graph(g, stream=side):
-                    for i in range(args.steps):
-                        fn(sets[i % nsets])
-            torch.cuda.synchronize()
-            g.replay()
-            torch.cuda.synchronize()
-            e0.record()
-            g.replay()
-            e1.record()
-            e1.synchronize()
-            graph_us = e0.elapsed_time(e1) * 1e3 / args.steps
-        except Exception as exc:  # capture unavailable: keep the eager figure
-            print(f"bench.py: graph capture failed ({exc}); using eager launches", file=sys.stderr)
-        return (graph_us if graph_us is not None else eager_us), eager_us   # microseconds per launch
+        graph_us = graph_wall_us = None
+        if not eager_only:
+            try:
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.stream(side):
+                    with torch.cuda.graph(g, stream=side):
+                        for i in range(args.steps):
+                            fn(sets[i % nsets])
+                torch.cuda.synchronize()
+                g.replay()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                e0.record()
+                g.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                graph_wall_us = (time.perf_counter() - t0) * 1e6 / args.steps
+                graph_us = e0.elapsed_time(e1) * 1e3 / args.steps
+            except Exception as exc:  # capture unavailable: keep the eager figures
+                print(f"bench.py: graph capture failed ({exc}); using eager launches", file=sys.stderr)
+        return dict(us=graph_us if graph_us is not None else eager_us, eager_us=eager_us,
+                    wall_us=graph_wall_us if graph_wall_us is not None else eager_wall_us,
+                    eager_wall_us=eager_wall_us, graph=graph_us is not None)
 
-    rotq_us, rotq_eager_us = time_kernel(rotq)
-    gemm_us, gemm_eager_us = time_kernel(gemm)
+    for i in range(args.warmup):
+        step(sets[i % nsets])
+    whole = time_region(step, eager_only=args.eager)
+    ms_per_step = whole["wall_us"] * 1e-3                   # host clock around exactly args.steps steps
+    tr = time_region(rotq, eager_only=args.eager)
+    tg = time_region(gemm, eager_only=args.eager)
+    rotq_us, rotq_eager_us, gemm_us, gemm_eager_us = tr["us"], tr["eager_us"], tg["us"], tg["eager_us"]
 
-    flops = 2.0 * T * N * K
-    rotq_bytes = rotq_algorithmic_bytes(T, K)
+    flops = sum(2.0 * T * n * k for _, k, n, _ in linears)
+    rotq_bytes = sum(rotq_algorithmic_bytes(T, k) for _, k, _, _ in linears)
+    weight_bytes = sum(n * k * (0.5 + 1.0 / 32.0) for _, k, n, _ in linears)
     rotq_gbps = rotq_bytes / (rotq_us * 1e-6) / 1e9
     gemm_tflops = flops / (gemm_us * 1e-6) / 1e12
     value = flops / (ms_per_step * 1e-3) / 1e12
+    headline = args.config == "c2_8b_down_prefill"
 
     result = {
         "metric": METRIC,
@@ -175,31 +204,39 @@ def main():
         "unit": "TFLOP/s (2*T*N*K per whole step: rotate+quantise, then GEMM)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5),
+        "ms_per_step_eager_launches": round(whole["eager_wall_us"] * 1e-3, 5),
+        "launch": "HIP graph replay of the timed steps" if whole["graph"] else "eager launches",
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "mxfp4 (E2M1 codes + E8M0 scales; fp32 rotation and accumulation)",
         "data": "synthetic",
-        "config": {"workload": args.config, "T": T, "K": K, "N": N, "output": cfg["out"],
-                   "buffer_sets": nsets, "rotation_blocks": G,
-                   "operand_layout": "tiled"},
+        "config": {"workload": args.config, "T": T,
+                   "linears": [{"name": nm, "K": k, "N": n} for nm, k, n, _ in linears],
+                   "output": cfg["out"], "buffer_sets": nsets, "operand_layout": "tiled"},
         "components": {
             "rotate_quantize": {"us": round(rotq_us, 2), "us_eager_launches": round(rotq_eager_us, 2),
-                                "GB/s": round(rotq_gbps, 1),
+                                "launches": len(linears), "GB/s": round(rotq_gbps, 1),
                                 "frac_hbm_peak": round(rotq_gbps / HBM_PEAK_GBPS, 4)},
             "mxfp4_gemm": {"us": round(gemm_us, 2), "us_eager_launches": round(gemm_eager_us, 2),
-                           "TFLOP/s": round(gemm_tflops, 1),
+                           "launches": len(linears), "TFLOP/s": round(gemm_tflops, 1),
                            "frac_mfma_peak": round(gemm_tflops / FP4_PEAK_TFLOPS, 4),
                            # N*K*(1/2 + 1/32) bytes of weights per launch: the decode-shape figure of merit
-                           "weight_stream_GB/s": round(N * K * (0.5 + 1.0 / 32.0) / (gemm_us * 1e-6) / 1e9, 1)},
+                           "weight_stream_GB/s": round(weight_bytes / (gemm_us * 1e-6) / 1e9, 1)},
         },
         "roofline": {"kernel": "mxfp4_gemm", "bound": "mfma", "achieved": round(gemm_tflops, 1),
                      "peak": FP4_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(gemm_tflops / FP4_PEAK_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC["gemm"] if args.config == "c2_8b_down_prefill" else None},
+                     "traffic": MEASURED_TRAFFIC["gemm"] if headline else None},
         "roofline_rotate_quantize": {"kernel": "rotq", "bound": "hbm", "achieved": round(rotq_gbps, 1),
                                      "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                      "frac": round(rotq_gbps / HBM_PEAK_GBPS, 4),
-                                     "traffic": MEASURED_TRAFFIC["rotq"] if args.config == "c2_8b_down_prefill" else None},
+                                     "traffic": MEASURED_TRAFFIC["rotq"] if headline else None},
     }
+    if T <= 32:
+        # decode shapes: the product streams the weights once, so HBM bounds it, not the matrix cores
+        result["roofline"] = {"kernel": "mxfp4_gemm (decode)", "bound": "hbm",
+                              "achieved": round(weight_bytes / (gemm_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS,
+                              "unit": "GB/s", "frac": round(weight_bytes / (gemm_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                              "traffic": None}
 
     # ---- the CPU oracle on a bounded sample of the same workload ---------------------------
     if not args.no_cpu_baseline:
@@ -210,7 +247,7 @@ def main():
         except Exception:
             threads = os.cpu_count() or 1
         Ts = min(T, 256)
-        s0 = sets[0]
+        s0 = sets[0][-1]
         bc_rm, bs_rm = duqpp.untile_operand(s0["bc"], s0["bs"], N, K)       # row-major view of the weights for the oracle
         bc_h, bs_h = bc_rm.cpu().numpy(), bs_rm.cpu().numpy()
         c0 = time.perf_counter()
@@ -220,10 +257,11 @@ def main():
         result["cpu_baseline"] = {
             "value": round(2.0 * Ts * N * K / (c1 - c0) / 1e12, 5), "unit": "TFLOP/s (whole step)",
             "cores": int(threads), "kind": "oracle", "seconds": round(c1 - c0, 2),
-            "sample": f"first {Ts} of {T} tokens, full K and N (rotate+quantise then fp64 product)"}
+            "sample": f"first {Ts} of {T} tokens of linear '{s0['name']}', full K={K} and N={N} "
+                      "(rotate+quantise then fp64 product)"}
         # the sampled rows double as a live parity check of what was timed
-        rotq(s0)
-        gemm(s0)
+        rotq1(s0)
+        gemm1(s0)
         torch.cuda.synchronize()
         y_dev = s0["y"][:Ts].float().cpu().numpy()
         ac_rm, as_rm = duqpp.untile_operand(s0["ac"], s0["asc"], T, K)

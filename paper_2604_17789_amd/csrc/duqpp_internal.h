@@ -29,9 +29,10 @@ struct RotqParams {
     int tiles_per_wg;
     int ngroups;         // ceil(ntiles / tiles_per_wg)
     int nchunks;         // column chunks (each covers waves*2 blocks)
+    int waves;           // wavefronts per workgroup
 };
 hipError_t launch_rotq(const RotqParams& p, hipStream_t stream);
-void plan_rotq(RotqParams& p);    // fills ntiles / tiles_per_wg / ngroups / nchunks
+void plan_rotq(RotqParams& p);    // fills ntiles / tiles_per_wg / ngroups / nchunks / waves
 
 struct QuantDbgParams {
     const float* y; int64_t ldy; int rows; int G; uint8_t* codes; uint8_t* scales;

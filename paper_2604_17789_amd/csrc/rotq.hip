@@ -109,7 +109,7 @@ __device__ __forceinline__ uint32_t quantize_group(const f32x16& acc, uint2& out
 
 __device__ __forceinline__ void logical_workgroup(int& logical) {
     // Workgroups are dealt round-robin to the 8 XCDs; renumber so that each XCD gets a
-    // contiguous range (same column chunk -> same R blocks and output lines in one L2).
+    // contiguous range of logical workgroups.
     int id = blockIdx.x, n = gridDim.x;
     int per = n / kNumXCD, rem = n % kNumXCD;
     int xcd = id % kNumXCD, slot = id / kNumXCD;
@@ -156,6 +156,18 @@ __device__ __forceinline__ void lds_barrier() {
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// s_waitcnt takes an immediate: wait until at most the largest constant <= n (n <= MAX) operations are
+// outstanding.  n is uniform over the wave.
+template <int MAX>
+__device__ __forceinline__ void wait_vmcnt_at_most(int n) {
+    if constexpr (MAX == 0) {
+        wait_vmcnt<0>();
+    } else {
+        if (n >= MAX) wait_vmcnt<MAX>();
+        else wait_vmcnt_at_most<MAX - 1>(n);
+    }
 }
 
 // Workgroup tile: 32 tokens x (WAVES * 2) blocks.  Per token row that is WAVES*128 bytes of
@@ -214,8 +226,8 @@ __global__ __launch_bounds__(WAVES * 64) void rotq_kernel(RotqParams p) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     int logical;
     logical_workgroup(logical);
-    const int chunk = logical / p.ngroups;
-    const int tg = logical % p.ngroups;
+    const int chunk = logical % p.nchunks;                   // neighbours on an XCD: neighbouring columns, same rows
+    const int tg = logical / p.nchunks;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int c = lane & 31, h = lane >> 5;
@@ -345,37 +357,160 @@ __global__ __launch_bounds__(WAVES * 64) void rotq_kernel(RotqParams p) {
     }
 }
 
+
+// ---- Tiled-output kernel: every wavefront runs a pipeline of its own ---------------------------
+// With the tiled operand layout a wave's output for one block is 512 contiguous bytes, so nothing has
+// to be exchanged between waves.  Each wave therefore owns two adjacent blocks (one 128-byte line per
+// token row) of a run of 32-token tiles, moves its own 4 KiB tiles by LDS-DMA into a private ring of
+// LDS stages and never meets a workgroup barrier: eight such pipelines per CU drift apart, and one
+// wave's matrix-core and convert work fills another's memory waits.
+// A tile is 32 rows x 8 chunks of 16 bytes; chunk q of row r is kept at position q ^ (r & 7) (applied
+// on the global side of the transfer), which makes the per-token reads conflict-free.
+// The output stores are asm statements so that their number per tile is fixed (kWaveStores): the waits
+// count outstanding vector-memory operations, which complete in issue order.
+constexpr int kWaveTileBytes = 4096;
+constexpr int kWaveStores = 3;             // two code stores and one scale store per tile
+
+__device__ __forceinline__ void store_b64(void* ptr, uint2 v) {
+    asm volatile("global_store_dwordx2 %0, %1, off" ::"v"(ptr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store_b16(void* ptr, uint32_t v) {
+    asm volatile("global_store_short %0, %1, off" ::"v"(ptr), "v"(v) : "memory");
+}
+
+__device__ __forceinline__ void issue_wave_tile(const RotqParams& p, uint32_t lds_stage, int tile, int pair, int lane) {
+    const int pos = lane & 7;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = 8 * i + (lane >> 3);                   // token row within the tile
+        int gch = pair * 8 + (pos ^ (r & 7));                // 16-byte chunk of the row that belongs at `pos`
+        if (gch >= p.G * 4) gch = 0;                         // padding groups: any valid address, output is masked
+        int row = tile * 32 + r;
+        if (row >= p.rows) row = p.rows - 1;                 // ragged last tile
+        const uint16_t* g = p.x + (int64_t)row * p.ldx + (int64_t)gch * 8;
+        __builtin_amdgcn_global_load_lds((global_void_ptr)g,
+                                         (lds_void_ptr)(uintptr_t)(lds_stage + i * 1024), 16, 0, 0);
+    }
+}
+
+template <int STAGES>
+__global__ __launch_bounds__(512) void rotq_wave_kernel(RotqParams p) {
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    int logical;
+    logical_workgroup(logical);
+    // Consecutive workgroups (which the renumbering keeps on one XCD) take consecutive column chunks of
+    // the same token rows: together they read whole rows of X, and their addresses spread over all L2
+    // channels -- workgroups that share a column chunk sit at the same offset in every row, and a row
+    // length that is a multiple of the channel interleave then sends them all to the same few channels.
+    const int chunk = logical % p.nchunks;
+    const int tg = logical / p.nchunks;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int c = lane & 31, h = lane >> 5;
+    const int pair = chunk * p.waves + wave;
+    if (pair * 2 >= p.GP) return;                            // no barrier anywhere: a spare wave just leaves
+    const int jt0 = pair * 2, jt1 = jt0 + 1;                 // < GP (GP is even)
+    const int j0 = jt0 < p.G ? jt0 : p.G - 1, j1 = jt1 < p.G ? jt1 : p.G - 1;
+
+    // token tiles are dealt to the ngroups runs as evenly as integers allow
+    const int tile0 = (int)((int64_t)tg * p.ntiles / p.ngroups);
+    const int tile1 = (int)((int64_t)(tg + 1) * p.ntiles / p.ngroups);
+    const uint32_t ring = lds_offset(lds) + wave * (STAGES * kWaveTileBytes);
+
+    // A stage is refilled as soon as its tile has been read into registers, so the ring holds exactly
+    // the tiles in flight.
+    constexpr int P = STAGES;
+#pragma unroll
+    for (int d = 0; d < P; ++d)
+        if (tile0 + d < tile1) issue_wave_tile(p, ring + d * kWaveTileBytes, tile0 + d, pair, lane);
+    // the rotation blocks arrive behind the first tiles instead of ahead of them
+    RotOperand op0, op1;
+    load_rot_operand(p.R + (int64_t)j0 * p.r_stride, c, h, op0);
+    load_rot_operand(p.R + (int64_t)j1 * p.r_stride, c, h, op1);
+
+    int stage = 0;
+    for (int tile = tile0; tile < tile1; ++tile) {
+        // This tile's four transfers have landed once at most the transfers issued after them (up to P - 1
+        // tiles) are outstanding: transfers complete in issue order.  Stores complete in no fixed order
+        // relative to them, so they are not counted; one that is still outstanding only makes the wait stricter.
+        const int ahead = tile1 - 1 - tile;
+        wait_vmcnt_at_most<4 * (P - 1)>(4 * (ahead < P - 1 ? ahead : P - 1));
+        const uint32_t in = ring + stage * kWaveTileBytes + c * 128;
+        u32x4 x0[2], x1[2];
+        lds_read4_b128(in + ((h ^ (c & 7)) << 4), in + (((2 + h) ^ (c & 7)) << 4),
+                       in + (((4 + h) ^ (c & 7)) << 4), in + (((6 + h) ^ (c & 7)) << 4),
+                       x0[0], x0[1], x1[0], x1[1]);
+        // this stage is free again (the reads above have returned): refill it P tiles ahead
+        if (ahead >= P) issue_wave_tile(p, ring + stage * kWaveTileBytes, tile + P, pair, lane);
+
+        f32x16 acc0 = rotate_tile(op0, x0);
+        f32x16 acc1 = rotate_tile(op1, x1);
+        uint2 o0, o1;
+        uint32_t byte0 = quantize_group(acc0, o0);
+        uint32_t byte1 = quantize_group(acc1, o1);
+
+        // rows past the end and groups past K are padding of the tiled layout: code 0, scale 127
+        const bool row_ok = tile * 32 + c < p.rows;
+        if (!row_ok || jt0 >= p.G) { o0 = make_uint2(0, 0); byte0 = 127; }
+        if (!row_ok || jt1 >= p.G) { o1 = make_uint2(0, 0); byte1 = 127; }
+        uint8_t* ct = p.codes + (((int64_t)tile * p.GP + jt0) * 32 + c) * 16 + 8 * h;
+        store_b64(ct, o0);
+        store_b64(ct + 512, o1);
+        // both half-waves hold the same two scale bytes and write them to the same place
+        uint8_t* st = p.scales + ((((int64_t)tile * (p.GP / 8) + jt0 / 8) * 2 + (jt0 % 8) / 4) * 32 + c) * 4 + (jt0 % 4);
+        store_b16(st, byte0 | (byte1 << 8));
+        stage = stage + 1 == STAGES ? 0 : stage + 1;
+    }
+}
+
 constexpr int kRotqStages = 4;             // 3 tiles in flight, one in use
+
+constexpr int kWaveStages = 2;             // per-wave ring of the tiled-output kernel: 2 tiles of 4 KiB in flight
+                                           // (deeper rings measured no faster at any of the benchmark shapes)
 
 void plan_rotq(RotqParams& p) {
     p.ntiles = (p.rows + 31) / 32;
-    const int cover = p.tiled ? p.GP : p.G;                  // the tiled layout's padding groups are written too
-    p.nchunks = (cover + kBlocksPerWG - 1) / kBlocksPerWG;
-    // One resident round: each workgroup keeps its R blocks in registers and walks as many token
+    if (p.tiled) {
+        // wave-private pipelines: a workgroup is `waves` independent waves on adjacent block pairs.
+        // Fewer waves per workgroup when the problem is too small to give every CU a full one.
+        const int npairs = p.GP / 2;
+        p.waves = 8;
+        while (p.waves > 1 && (int64_t)((npairs + p.waves - 1) / p.waves) * p.ntiles < kNumCU) p.waves /= 2;
+        p.nchunks = (npairs + p.waves - 1) / p.waves;
+    } else {
+        p.waves = kRotqWaves;
+        p.nchunks = (p.G + kBlocksPerWG - 1) / kBlocksPerWG;
+    }
+    // One resident round: each wave keeps its R blocks in registers and walks as many token
     // tiles as the problem allows, so the fetch and split of R is amortised.
-    const int64_t slots = (int64_t)kNumCU * kRotqWGPerCU;
+    const int64_t slots = (int64_t)kNumCU * kRotqWGPerCU * (kRotqWaves / p.waves);
     int groups = (int)(slots / p.nchunks);
     if (groups < 1) groups = 1;
     if (groups > p.ntiles) groups = p.ntiles;
     p.tiles_per_wg = (p.ntiles + groups - 1) / groups;
-    p.ngroups = (p.ntiles + p.tiles_per_wg - 1) / p.tiles_per_wg;
+    p.ngroups = p.tiled ? groups : (p.ntiles + p.tiles_per_wg - 1) / p.tiles_per_wg;
 }
 
 hipError_t launch_rotq(const RotqParams& p, hipStream_t stream) {
     using TL = RotqTile<kRotqWaves, kRotqStages>;
     static std::atomic<int> configured{0};
     auto kern_rm = rotq_kernel<kRotqWaves, kRotqStages, false>;
-    auto kern_t = rotq_kernel<kRotqWaves, kRotqStages, true>;
+    auto kern_t = rotq_wave_kernel<kWaveStages>;
+    constexpr int kWaveLdsMax = 8 * kWaveStages * kWaveTileBytes;
     if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)kern_rm, hipFuncAttributeMaxDynamicSharedMemorySize, TL::kLdsBytes);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void*)kern_t, hipFuncAttributeMaxDynamicSharedMemorySize, TL::kLdsBytes);
+        e = hipFuncSetAttribute((const void*)kern_t, hipFuncAttributeMaxDynamicSharedMemorySize, kWaveLdsMax);
         if (e != hipSuccess) return e;
         configured.store(1, std::memory_order_release);
     }
-    dim3 grid((unsigned)((int64_t)p.nchunks * p.ngroups)), block(kRotqWaves * 64);
-    if (p.tiled) hipLaunchKernelGGL(kern_t, grid, block, TL::kLdsBytes, stream, p);
-    else hipLaunchKernelGGL(kern_rm, grid, block, TL::kLdsBytes, stream, p);
+    dim3 grid((unsigned)((int64_t)p.nchunks * p.ngroups));
+    if (p.tiled) {
+        if (p.waves < 1 || p.waves > 8) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(kern_t, grid, dim3(p.waves * 64), p.waves * kWaveStages * kWaveTileBytes, stream, p);
+    } else {
+        hipLaunchKernelGGL(kern_rm, grid, dim3(kRotqWaves * 64), TL::kLdsBytes, stream, p);
+    }
     return hipGetLastError();
 }
 

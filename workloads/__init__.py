@@ -8,6 +8,7 @@ oracle and the HIP library receive these buffers as plain inputs.
 from .generators import (  # noqa: F401
     CONFIGS,
     LAYER_SET_8B,
+    LAYER_SET_CONFIGS,
     OutlierSpec,
     bf16_bits_to_f32,
     f32_to_bf16_bits,

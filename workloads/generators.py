@@ -146,3 +146,9 @@ LAYER_SET_8B: List[Tuple[str, int, int, bool]] = [
     ("up", 4096, 14336, False),
     ("down", 14336, 4096, True),
 ]
+# the whole set as one workload: T tokens through all seven linears, each with its own rotation; inputs of
+# the linears marked True carry 8 seeded outlier channels x100, outputs are bf16
+LAYER_SET_CONFIGS = {
+    "c5_8b_layer_set_T8192": dict(T=8192, layers=LAYER_SET_8B, w_std=0.02, out="bf16",
+                                  outliers=(OutlierSpec(8, 100.0),)),
+}
