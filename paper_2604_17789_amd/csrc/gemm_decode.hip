@@ -2,7 +2,10 @@
 // single row tile and the product is bound by streaming the weights once from HBM (N * K * 17/32
 // bytes).  Tiled operand layout, same instruction and K permutation as the prefill kernel.
 //
-// One workgroup of 8 waves per weight row tile (32 output channels).  The waves split K: each owns a
+// One workgroup of 8 waves per ROWS = 32 or 16 output channels of a weight row tile: the streaming rate
+// a single CU sustains is a small fraction of the chip's, so the launch wants at least one workgroup per
+// CU, and with fewer row tiles than CUs each tile is cut into 2 workgroups.  Such a workgroup still issues the
+// 32-row instruction; its lanes r >= ROWS load nothing, feed zeros, and their results are dropped.  The waves split K: each owns a
 // contiguous range of K steps, loads its weight fragments straight from global memory into registers
 // (512 contiguous bytes per half-wave and load, every byte read once chip-wide), its activation
 // fragments from the L2-resident activation tile, and accumulates one 32 x 32 tile.  The eight
@@ -31,18 +34,25 @@ struct DecStep {
     uint32_t sa, sb;
 };
 
+template <int ROWS>
 __device__ __forceinline__ void dec_load(DecStep& d, const uint8_t* a_codes, const uint8_t* a_scales,
                                          const uint8_t* b_codes, const uint8_t* b_scales, int step, int lane_code,
-                                         int lane4) {
+                                         int lane4, int lane_code_b, int lane4_b, int r) {
     const uint8_t* pa = a_codes + (int64_t)step * 4096 + lane_code;
-    const uint8_t* pb = b_codes + (int64_t)step * 4096 + lane_code;
+    const uint8_t* pb = b_codes + (int64_t)step * 4096 + lane_code_b;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        d.a[i] = *(const u32x4*)(pa + i * 512);
-        d.b[i] = __builtin_nontemporal_load((const u32x4*)(pb + i * 512));   // weights are read once
-    }
+    for (int i = 0; i < 4; ++i) d.a[i] = *(const u32x4*)(pa + i * 512);
     d.sa = *(const uint32_t*)(a_scales + (int64_t)step * 256 + lane4);
-    d.sb = *(const uint32_t*)(b_scales + (int64_t)step * 256 + lane4);
+    // weights are read once; lanes beyond the workgroup's rows load nothing and feed zeros
+    if (ROWS == 32 || r < ROWS) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) d.b[i] = __builtin_nontemporal_load((const u32x4*)(pb + i * 512));
+        d.sb = *(const uint32_t*)(b_scales + (int64_t)step * 256 + lane4_b);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) d.b[i] = u32x4{0u, 0u, 0u, 0u};
+        d.sb = 0x7F7F7F7Fu;
+    }
 }
 
 __device__ __forceinline__ uint16_t dec_f32_to_bf16_rne(float f) {
@@ -51,13 +61,16 @@ __device__ __forceinline__ uint16_t dec_f32_to_bf16_rne(float f) {
     return (uint16_t)(u >> 16);
 }
 
-template <bool OUT_BF16>
+template <bool OUT_BF16, int ROWS>
 __global__ __launch_bounds__(kDecWaves * 64) void gemm_decode_kernel(TiledGemmParams p) {
+    static_assert(ROWS == 32 || ROWS == 16, "a row tile is cut into 1 or 2 workgroups");
     __shared__ float part[kDecWaves][16][64];              // [wave][accumulator register][lane]
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int r = lane & 31, g = lane >> 5;
-    const int rt = blockIdx.x;                             // weight row tile
+    constexpr int kCuts = 32 / ROWS;
+    const int rt = blockIdx.x / kCuts;                     // weight row tile
+    const int rb = (blockIdx.x % kCuts) * ROWS + (r & (ROWS - 1));   // row of the tile lane r < ROWS supplies
     const int NI = p.GP / 8;
     const int per = (NI + kDecWaves - 1) / kDecWaves;
     const int s0 = wave * per;
@@ -66,18 +79,21 @@ __global__ __launch_bounds__(kDecWaves * 64) void gemm_decode_kernel(TiledGemmPa
 
     const uint8_t* b_codes = p.b_codes + (int64_t)rt * p.GP * 512;
     const uint8_t* b_scales = p.b_scales + (int64_t)rt * NI * 256;
-    const int lane_code = g * 2048 + r * 16;               // group 4 g + i of row r sits at (4 g + i) * 512 + r * 16
-    const int lane4 = lane * 4;
+    // A operand (activations): group 4 g + i of row r sits at (4 g + i) * 512 + r * 16, its scale word at
+    // (32 g + r) * 4; B operand (weights): the same with row rb
+    const int lane_code = g * 2048 + r * 16, lane_code_b = g * 2048 + rb * 16;
+    const int lane4 = lane * 4, lane4_b = (g * 32 + rb) * 4;
 
     f32x16 acc;
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0.f;
 
-    // two steps in flight per wave: the loads of step s + 1 are issued before the MFMAs of step s
+    // two steps in flight per wave: the loads of step s + 1 are issued before the MFMAs of step s.
+    // (Deeper register rings measured slower: they cost the occupancy that hides the latency better.)
     DecStep cur, nxt;
-    if (s0 < s1) dec_load(cur, p.a_codes, p.a_scales, b_codes, b_scales, s0, lane_code, lane4);
+    if (s0 < s1) dec_load<ROWS>(cur, p.a_codes, p.a_scales, b_codes, b_scales, s0, lane_code, lane4, lane_code_b, lane4_b, r);
     for (int s = s0; s < s1; ++s) {
-        if (s + 1 < s1) dec_load(nxt, p.a_codes, p.a_scales, b_codes, b_scales, s + 1, lane_code, lane4);
+        if (s + 1 < s1) dec_load<ROWS>(nxt, p.a_codes, p.a_scales, b_codes, b_scales, s + 1, lane_code, lane4, lane_code_b, lane4_b, r);
         DUQPP_DEC_MFMA(acc, cur.a[0], cur.b[0], cur.sa, cur.sb, 0);
         DUQPP_DEC_MFMA(acc, cur.a[1], cur.b[1], cur.sa, cur.sb, 1);
         DUQPP_DEC_MFMA(acc, cur.a[2], cur.b[2], cur.sa, cur.sb, 2);
@@ -87,7 +103,7 @@ __global__ __launch_bounds__(kDecWaves * 64) void gemm_decode_kernel(TiledGemmPa
 #pragma unroll
     for (int e = 0; e < 16; ++e) part[wave][e][lane] = acc[e];
     __syncthreads();
-    // acc[e] of lane (r, g): token 8 (e / 4) + 4 g + e % 4, output channel 32 rt + r.
+    // acc[e] of lane (r, g): token 8 (e / 4) + 4 g + e % 4, output channel 32 rt + rb (lanes r < ROWS).
     // 1024 outputs, 512 threads: thread t sums register e = t / 64 and e + 8 of lane t % 64 over the waves.
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -96,18 +112,27 @@ __global__ __launch_bounds__(kDecWaves * 64) void gemm_decode_kernel(TiledGemmPa
 #pragma unroll
         for (int w = 0; w < kDecWaves; ++w) sum += part[w][e][lane];
         const int tok = 8 * (e / 4) + 4 * g + (e % 4);
-        const int col = rt * 32 + r;
-        if (tok < p.T && col < p.N) {
+        const int col = rt * 32 + rb;
+        if (r < ROWS && tok < p.T && col < p.N) {
             if (OUT_BF16) ((uint16_t*)p.y)[(int64_t)tok * p.ldy + col] = dec_f32_to_bf16_rne(sum);
             else ((float*)p.y)[(int64_t)tok * p.ldy + col] = sum;
         }
     }
 }
 
+template <int ROWS>
+static void launch_decode_rows(const TiledGemmParams& p, unsigned tiles, hipStream_t stream) {
+    dim3 grid(tiles * (32 / ROWS)), block(kDecWaves * 64);
+    if (p.out_bf16) hipLaunchKernelGGL((gemm_decode_kernel<true, ROWS>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((gemm_decode_kernel<false, ROWS>), grid, block, 0, stream, p);
+}
+
 hipError_t launch_gemm_decode(const TiledGemmParams& p, hipStream_t stream) {
-    dim3 grid((unsigned)((p.N + 31) / 32)), block(kDecWaves * 64);
-    if (p.out_bf16) hipLaunchKernelGGL(gemm_decode_kernel<true>, grid, block, 0, stream, p);
-    else hipLaunchKernelGGL(gemm_decode_kernel<false>, grid, block, 0, stream, p);
+    const unsigned tiles = (unsigned)((p.N + 31) / 32);
+    // Measured at N = 4096, K = 14336: halving the row tiles (256 workgroups instead of 128) gains 13 %;
+    // quartering them, 16 waves per workgroup or deeper register rings all lose.
+    if (tiles >= (unsigned)kNumCU) launch_decode_rows<32>(p, tiles, stream);
+    else launch_decode_rows<16>(p, tiles, stream);
     return hipGetLastError();
 }
 
