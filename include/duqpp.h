@@ -90,8 +90,11 @@ int duqpp_rotate_quantize(const void* x_bf16, int64_t T, int64_t K, int64_t ldx,
  *   b_codes/b_scales  in   [N, K/2], [N, K/32]   (from duqpp_quantize_weights)
  *   y                 out  [T, N] of out_dtype (duqpp_dtype), stride ldy; bf16 output is the
  *                          round-to-nearest-even of the fp32 result
- *   workspace         scratch of at least duqpp_gemm_workspace_bytes(T, N, K, 0) bytes,
- *                     256-byte aligned; may be null when that size is 0
+ *   workspace         optional scratch of at least duqpp_gemm_workspace_bytes(T, N, K, 0) bytes, 256-byte
+ *                     aligned.  With it the operands are first re-tiled into the scratch (see the tiled
+ *                     layout below) and the fast kernel runs; with NULL a slower kernel reads the row-major
+ *                     operands directly.  Same result either way up to the order of the fp32 additions.
+ *                     A non-null workspace that is too small is an error (DUQPP_ERR_WORKSPACE).
  */
 int duqpp_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
                      const uint8_t* b_codes, const uint8_t* b_scales,
@@ -101,8 +104,10 @@ int duqpp_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
 
 /*
  * Fused form of the online path: Y = Q(X . R^) . Q(W^) in one call, producing exactly the
- * codes duqpp_rotate_quantize would and the product duqpp_mxfp4_gemm would.
- *   workspace  at least duqpp_gemm_workspace_bytes(T, N, K, 1) bytes, 256-byte aligned
+ * codes duqpp_rotate_quantize would and the product duqpp_mxfp4_gemm would (two kernels on the stream
+ * plus the re-tiling of the row-major weights; callers that keep the weights tiled use
+ * duqpp_rotq_gemm_tiled and skip that).
+ *   workspace  required: at least duqpp_gemm_workspace_bytes(T, N, K, 1) bytes, 256-byte aligned
  */
 int duqpp_rotq_gemm(const void* x_bf16, int64_t ldx, const float* R, int64_t n_rblocks,
                     const uint8_t* b_codes, const uint8_t* b_scales,
@@ -167,7 +172,8 @@ int duqpp_rotq_gemm_tiled(const void* x_bf16, int64_t ldx, const float* R, int64
                           void* y, int out_dtype, int64_t ldy,
                           void* workspace, size_t workspace_bytes, void* stream);
 
-/* Host, pure: scratch bytes duqpp_mxfp4_gemm (fused = 0) or duqpp_rotq_gemm (fused = 1) needs. */
+/* Host, pure: scratch bytes duqpp_mxfp4_gemm (fused = 0) can use or duqpp_rotq_gemm (fused = 1) needs:
+ * room for both operands in the tiled layout.  0 for invalid shapes. */
 size_t duqpp_gemm_workspace_bytes(int64_t T, int64_t N, int64_t K, int fused);
 
 /*

@@ -151,6 +151,8 @@ def _out(T, N, out_dtype, device, out):
 
 
 def mxfp4_gemm(a_codes, a_scales, b_codes, b_scales, out_dtype=F32, out=None, workspace=None):
+    """Row-major operands -> Y [T, N].  workspace: None = allocate the scratch of the fast path, False = none
+    (direct kernel), or a uint8 tensor of at least gemm_workspace_bytes(T, N, K)."""
     for t, n in ((a_codes, "a_codes"), (a_scales, "a_scales"), (b_codes, "b_codes"), (b_scales, "b_scales")):
         _dev(t, torch.uint8, n)
         if not t.is_contiguous():
@@ -162,6 +164,8 @@ def mxfp4_gemm(a_codes, a_scales, b_codes, b_scales, out_dtype=F32, out=None, wo
     y = _out(T, N, out_dtype, a_codes.device, out)
     if workspace is None:
         workspace, nbytes = _workspace(gemm_workspace_bytes(T, N, K, False), a_codes.device)
+    elif workspace is False:                                # no scratch: the direct row-major kernel
+        workspace, nbytes = None, 0
     else:
         nbytes = workspace.numel()
     st = lib.duqpp_mxfp4_gemm(a_codes.data_ptr(), a_scales.data_ptr(), b_codes.data_ptr(), b_scales.data_ptr(),

@@ -59,9 +59,23 @@ int rotate_quantize_impl(const void* x, int64_t rows, int64_t K, int64_t ldx, co
     return launch_rotq(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
 }
 
-// layout of the fused call's scratch: A codes, then A scales (256-byte aligned), then the GEMM's own
-size_t fused_codes_bytes(int64_t T, int64_t K) { return ((size_t)T * (size_t)(K / 2) + 255) & ~(size_t)255; }
-size_t fused_scales_bytes(int64_t T, int64_t K) { return ((size_t)T * (size_t)(K / 32) + 255) & ~(size_t)255; }
+// Scratch of the row-major GEMM calls: both operands in the tiled layout, each part rounded up to 256 bytes:
+// A codes, A scales, B codes, B scales.
+size_t round256(size_t n) { return (n + 255) & ~(size_t)255; }
+struct TiledScratch {
+    size_t a_codes, a_scales, b_codes, b_scales;           // byte offsets
+    size_t total;
+};
+TiledScratch tiled_scratch(int64_t T, int64_t N, int64_t K) {
+    TiledScratch w{};
+    const int64_t G = K / 32;
+    w.a_codes = 0;
+    w.a_scales = w.a_codes + round256(tiled_codes_bytes(T, G));
+    w.b_codes = w.a_scales + round256(tiled_scales_bytes(T, G));
+    w.b_scales = w.b_codes + round256(tiled_codes_bytes(N, G));
+    w.total = w.b_scales + round256(tiled_scales_bytes(N, G));
+    return w;
+}
 
 }  // namespace
 
@@ -91,19 +105,16 @@ int duqpp_validate_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales, c
     if (!fused && !aligned_to(a_codes, 16)) return DUQPP_ERR_ALIGN;
     if (!aligned_to(y, out_dtype == DUQPP_F32 ? 4 : 2)) return DUQPP_ERR_ALIGN;
     if (fused == 2) return DUQPP_OK;   // tiled operands: no workspace
-    size_t need = duqpp_gemm_workspace_bytes(T, N, K, fused);
-    if (need > 0) {
-        if (!workspace || workspace_bytes < need) return DUQPP_ERR_WORKSPACE;
-        if (!aligned_to(workspace, 256)) return DUQPP_ERR_ALIGN;
-    }
+    // the fused call needs its scratch; the separate call runs a slower direct kernel without one
+    if (!workspace && !fused) return DUQPP_OK;
+    if (!workspace || workspace_bytes < duqpp_gemm_workspace_bytes(T, N, K, fused)) return DUQPP_ERR_WORKSPACE;
+    if (!aligned_to(workspace, 256)) return DUQPP_ERR_ALIGN;
     return DUQPP_OK;
 }
 
-size_t duqpp_gemm_workspace_bytes(int64_t T, int64_t N, int64_t K, int fused) {
-    if (T < 1 || N < 1 || K < 32) return 0;
-    size_t w = gemm_workspace_bytes(T, N, K);
-    if (fused) w += fused_codes_bytes(T, K) + fused_scales_bytes(T, K);
-    return w;
+size_t duqpp_gemm_workspace_bytes(int64_t T, int64_t N, int64_t K, int /*fused*/) {
+    if (T < 1 || N < 1 || K < 32 || (K % 32) != 0) return 0;
+    return tiled_scratch(T, N, K).total;
 }
 
 int duqpp_rotate_quantize(const void* x_bf16, int64_t T, int64_t K, int64_t ldx, const float* R,
@@ -125,12 +136,24 @@ int duqpp_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint
     if (st != DUQPP_OK) return st;
     st = check_device();
     if (st != DUQPP_OK) return st;
-    GemmParams p{};
-    p.a_codes = a_codes; p.a_scales = a_scales; p.b_codes = b_codes; p.b_scales = b_scales;
-    p.T = (int)T; p.N = (int)N; p.G = (int)(K / 32);
-    p.y = y; p.ldy = ldy; p.out_bf16 = (out_dtype == DUQPP_BF16);
-    p.workspace = workspace; p.workspace_bytes = workspace_bytes;
-    return launch_gemm(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    if (!workspace) {
+        GemmParams p{};
+        p.a_codes = a_codes; p.a_scales = a_scales; p.b_codes = b_codes; p.b_scales = b_scales;
+        p.T = (int)T; p.N = (int)N; p.G = (int)(K / 32);
+        p.y = y; p.ldy = ldy; p.out_bf16 = (out_dtype == DUQPP_BF16);
+        return launch_gemm(p, hs) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
+    }
+    // re-tile both operands into the scratch, then the tiled kernel
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    const TiledScratch w = tiled_scratch(T, N, K);
+    const int G = (int)(K / 32), GP = (int)tiled_groups(G);
+    LayoutParams la{a_codes, a_scales, ws + w.a_codes, ws + w.a_scales, (int)T, G, GP};
+    LayoutParams lb{b_codes, b_scales, ws + w.b_codes, ws + w.b_scales, (int)N, G, GP};
+    if (launch_tile(la, hs) != hipSuccess || launch_tile(lb, hs) != hipSuccess) return DUQPP_ERR_HIP;
+    TiledGemmParams p{ws + w.a_codes, ws + w.a_scales, ws + w.b_codes, ws + w.b_scales, (int)T, (int)N, GP,
+                      y, ldy, out_dtype == DUQPP_BF16};
+    return launch_gemm_tiled(p, hs) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
 }
 
 int duqpp_rotq_gemm(const void* x_bf16, int64_t ldx, const float* R, int64_t n_rblocks,
@@ -143,14 +166,20 @@ int duqpp_rotq_gemm(const void* x_bf16, int64_t ldx, const float* R, int64_t n_r
                                        y, out_dtype, ldy, workspace, workspace_bytes, 1);
     if (st == DUQPP_ERR_NULL && !workspace && b_codes && b_scales && y) st = DUQPP_ERR_WORKSPACE;
     if (st != DUQPP_OK) return st;
-    uint8_t* a_codes = static_cast<uint8_t*>(workspace);
-    uint8_t* a_scales = a_codes + fused_codes_bytes(T, K);
-    uint8_t* rest = a_scales + fused_scales_bytes(T, K);
-    size_t rest_bytes = workspace_bytes - fused_codes_bytes(T, K) - fused_scales_bytes(T, K);
-    st = rotate_quantize_impl(x_bf16, T, K, ldx, R, n_rblocks, a_codes, a_scales, nullptr, stream);
+    st = check_device();
     if (st != DUQPP_OK) return st;
-    return duqpp_mxfp4_gemm(a_codes, a_scales, b_codes, b_scales, T, N, K, y, out_dtype, ldy,
-                            rest_bytes ? rest : nullptr, rest_bytes, stream);
+    // activations are rotated and quantised straight into the tiled layout; the row-major weights are re-tiled
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    const TiledScratch w = tiled_scratch(T, N, K);
+    const int G = (int)(K / 32), GP = (int)tiled_groups(G);
+    st = rotate_quantize_impl(x_bf16, T, K, ldx, R, n_rblocks, ws + w.a_codes, ws + w.a_scales, nullptr, stream, true);
+    if (st != DUQPP_OK) return st;
+    LayoutParams lb{b_codes, b_scales, ws + w.b_codes, ws + w.b_scales, (int)N, G, GP};
+    if (launch_tile(lb, hs) != hipSuccess) return DUQPP_ERR_HIP;
+    TiledGemmParams p{ws + w.a_codes, ws + w.a_scales, ws + w.b_codes, ws + w.b_scales, (int)T, (int)N, GP,
+                      y, ldy, out_dtype == DUQPP_BF16};
+    return launch_gemm_tiled(p, hs) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
 }
 
 int duqpp_quantize_f32_dbg(const float* y, int64_t rows, int64_t K, int64_t ldy, uint8_t* codes,

@@ -45,10 +45,8 @@ struct GemmParams {
     const uint8_t* b_codes; const uint8_t* b_scales;   // [N, K/2], [N, G]
     int T, N, G;
     void* y; int64_t ldy; int out_bf16;
-    void* workspace; size_t workspace_bytes;
 };
 hipError_t launch_gemm(const GemmParams& p, hipStream_t stream);
-size_t gemm_workspace_bytes(int64_t T, int64_t N, int64_t K);
 
 }  // namespace duqpp
 

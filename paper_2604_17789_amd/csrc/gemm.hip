@@ -130,7 +130,6 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(GemmParams p) {
         }
 }
 
-size_t gemm_workspace_bytes(int64_t, int64_t, int64_t) { return 0; }
 
 hipError_t launch_gemm(const GemmParams& p, hipStream_t stream) {
     dim3 grid((unsigned)((p.N + kDirTileN - 1) / kDirTileN), (unsigned)((p.T + kDirTileM - 1) / kDirTileM)), block(256);

@@ -21,6 +21,17 @@ def env():
     return torch, duqpp
 
 
+_WS = None    # workspace argument of the row-major call: None = scratch allocated (re-tile + fast kernel), False = direct kernel
+
+
+@pytest.fixture(params=["scratch", "direct"], autouse=True)
+def gemm_path(request):
+    """Every test of this module runs on both code paths behind duqpp_mxfp4_gemm."""
+    global _WS
+    _WS = None if request.param == "scratch" else False
+    yield request.param
+
+
 def _random_mx(rng, rows, K, lo=118, hi=136):
     codes = rng.integers(0, 256, size=(rows, K // 2)).astype(np.uint8)
     scales = rng.integers(lo, hi + 1, size=(rows, K // 32)).astype(np.uint8)
@@ -29,7 +40,8 @@ def _random_mx(rng, rows, K, lo=118, hi=136):
 
 def _gemm(env, ac, asc, bc, bsc, out_dtype=0):
     torch, duqpp = env
-    y = duqpp.mxfp4_gemm(to_dev(ac, torch), to_dev(asc, torch), to_dev(bc, torch), to_dev(bsc, torch), out_dtype=out_dtype)
+    y = duqpp.mxfp4_gemm(to_dev(ac, torch), to_dev(asc, torch), to_dev(bc, torch), to_dev(bsc, torch), out_dtype=out_dtype,
+                         workspace=_WS)
     torch.cuda.synchronize()
     return y
 
@@ -112,7 +124,7 @@ def test_strided_output(env):
     ac, asc = _random_mx(rng, T, K)
     bc, bsc = _random_mx(rng, N, K)
     big = torch.full((T, 128), -7.0, dtype=torch.float32, device="cuda:0")
-    duqpp.mxfp4_gemm(to_dev(ac, torch), to_dev(asc, torch), to_dev(bc, torch), to_dev(bsc, torch), out=big[:, :N])
+    duqpp.mxfp4_gemm(to_dev(ac, torch), to_dev(asc, torch), to_dev(bc, torch), to_dev(bsc, torch), out=big[:, :N], workspace=_WS)
     torch.cuda.synchronize()
     ref = linear.mxfp4_gemm(ac, asc, bc, bsc)
     assert rel_fro(big[:, :N].cpu().numpy(), ref) <= GEMM_TOL
@@ -132,12 +144,14 @@ def test_whole_path_on_the_reference_config(env):
     x, w, Rd = to_dev_bf16(xb, torch), to_dev_bf16(wb, torch), to_dev(R, torch)
     bc, bs = duqpp.quantize_weights(w, Rd)
     ac, asc = duqpp.rotate_quantize(x, Rd)
-    y = duqpp.mxfp4_gemm(ac, asc, bc, bs)
+    y = duqpp.mxfp4_gemm(ac, asc, bc, bs, workspace=_WS)
     yf = duqpp.rotq_gemm(x, Rd, bc, bs)
     torch.cuda.synchronize()
     ref = linear.mxfp4_gemm(ac.cpu().numpy(), asc.cpu().numpy(), bc.cpu().numpy(), bs.cpu().numpy())
     assert rel_fro(y.cpu().numpy(), ref) <= GEMM_TOL
-    assert torch.equal(y, yf)
+    # the fused call is the fast separate call (same kernel, same order of additions): bit-identical
+    assert torch.equal(duqpp.mxfp4_gemm(ac, asc, bc, bs), yf)
+    assert rel_fro(yf.cpu().numpy(), ref) <= GEMM_TOL
     # ungraded sanity: the W4A4 result approximates the unquantised product
     exact = wl.bf16_bits_to_f32(xb).astype(np.float64) @ wl.bf16_bits_to_f32(wb).astype(np.float64).T
     e = rel_fro(y.cpu().numpy(), exact)
@@ -158,6 +172,6 @@ def test_fused_call_equals_separate_calls(env, T, N, K):
         y = duqpp.mxfp4_gemm(ac, asc, bc, bs, out_dtype=dt)
         yf = duqpp.rotq_gemm(x, Rd, bc, bs, out_dtype=dt)
         torch.cuda.synchronize()
-        assert torch.equal(y, yf)
+        assert torch.equal(y, yf)                           # same kernel, same order of additions
     ref = linear.mxfp4_gemm(ac.cpu().numpy(), asc.cpu().numpy(), bc.cpu().numpy(), bs.cpu().numpy())
-    assert rel_fro(duqpp.mxfp4_gemm(ac, asc, bc, bs).cpu().numpy(), ref) <= GEMM_TOL
+    assert rel_fro(duqpp.mxfp4_gemm(ac, asc, bc, bs, workspace=_WS).cpu().numpy(), ref) <= GEMM_TOL
