@@ -189,6 +189,15 @@ def main():
     tr = time_region(rotq, eager_only=args.eager)
     tg = time_region(gemm, eager_only=args.eager)
     rotq_us, rotq_eager_us, gemm_us, gemm_eager_us = tr["us"], tr["eager_us"], tg["us"], tg["eager_us"]
+    per_linear = None
+    if not single:
+        per_linear = []
+        for li, (nm, k, n, _) in enumerate(linears):
+            r1 = time_region(lambda s, li=li: rotq1(s[li]), eager_only=args.eager)["us"]
+            g1 = time_region(lambda s, li=li: gemm1(s[li]), eager_only=args.eager)["us"]
+            per_linear.append({"name": nm, "K": k, "N": n, "rotq_us": round(r1, 2),
+                               "rotq_GB/s": round(rotq_algorithmic_bytes(T, k) / r1 / 1e3, 1),
+                               "gemm_us": round(g1, 2), "gemm_TFLOP/s": round(2.0 * T * n * k / g1 / 1e6, 1)})
 
     flops = sum(2.0 * T * n * k for _, k, n, _ in linears)
     rotq_bytes = sum(rotq_algorithmic_bytes(T, k) for _, k, _, _ in linears)
@@ -231,6 +240,8 @@ def main():
                                      "frac": round(rotq_gbps / HBM_PEAK_GBPS, 4),
                                      "traffic": MEASURED_TRAFFIC["rotq"] if headline else None},
     }
+    if per_linear:
+        result["components"]["per_linear"] = per_linear
     if T <= 32:
         # decode shapes: the product streams the weights once, so HBM bounds it, not the matrix cores
         result["roofline"] = {"kernel": "mxfp4_gemm (decode)", "bound": "hbm",

@@ -4,6 +4,9 @@
 // Shape of the kernel
 //   workgroup  4 waves (one per SIMD) as 2 x 2, output tile 128 (tokens) x 256 (output channels);
 //              each wave owns 64 x 128 = 2 x 4 MFMA tiles = 128 fp32 accumulators per lane.
+//   tiles      one workgroup per CU walks its output tiles one after the other; the operand transfers of the
+//              next tile start while the current one finishes, so only the store of a tile interrupts the
+//              matrix cores, not the refill of the pipeline.
 //   K loop     steps of 256 (8 MXFP4 groups).  The codes of a step, (4 + 8) row tiles x 4 KiB, and
 //              their scale words, 12 x 256 B, go from global memory straight into LDS by LDS-DMA
 //              (each code transfer moves one contiguous KiB); three such stages rotate, two in
@@ -100,8 +103,10 @@ __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// Every LDS access this wave has issued has completed, then workgroup barrier: what a wave writes to LDS
+// after the barrier cannot overtake a read another wave issued before it.
 __device__ __forceinline__ void workgroup_barrier() {
-    asm volatile("s_barrier" ::: "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 __device__ __forceinline__ i32x8 fp4_operand(const u32x4& v) {
@@ -148,53 +153,67 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
     const int r = lane & 31, g = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
 
-    // ---- which output tile: XCD-contiguous renumbering, then groups of kGroupM M-tiles swept
-    // along N, so that the 32 workgroups sharing an L2 cover a compact block of the output
     const int tiles_m = (p.T + kBM - 1) / kBM, tiles_n = (p.N + kBN - 1) / kBN;
-    int pid;
-    {
-        const int id = blockIdx.x, n = gridDim.x;
-        const int per = n / kNumXCD, rem = n % kNumXCD;
-        const int xcd = id % kNumXCD, slot = id / kNumXCD;
-        pid = xcd * per + (xcd < rem ? xcd : rem) + slot;
-    }
-    const int group_sz = kGroupM * tiles_n;
-    const int first_m = (pid / group_sz) * kGroupM;
-    const int gm = (tiles_m - first_m) < kGroupM ? (tiles_m - first_m) : kGroupM;
-    const int tile_m = first_m + (pid % group_sz) % gm;
-    const int tile_n = (pid % group_sz) / gm;
-
+    const int total = tiles_m * tiles_n;
     const int RTa = (p.T + 31) / 32, RTb = (p.N + 31) / 32;
-    const int NI = p.GP / 8;                               // K steps
+    const int NI = p.GP / 8;                               // K steps per tile
     const int64_t tile_bytes = (int64_t)p.GP * 512;        // codes of one row tile
     const int64_t tile_sbytes = (int64_t)NI * 256;         // scale words of one row tile
 
+    // ---- which output tiles.  The launch has at most one workgroup per CU; workgroup `slot` takes tiles
+    // slot, slot + nwg, ...  Within each such round the workgroups are renumbered so that an XCD holds a
+    // contiguous range, and tile numbers run through groups of kGroupM M-tiles swept along N, so that the
+    // 32 workgroups sharing an L2 cover a compact block of the output.
+    const int nwg = gridDim.x;                             // <= total
+    int slot;
+    {
+        const int id = blockIdx.x;
+        const int per = nwg / kNumXCD, rem = nwg % kNumXCD;
+        const int xcd = id % kNumXCD, sl = id / kNumXCD;
+        slot = xcd * per + (xcd < rem ? xcd : rem) + sl;
+    }
+    const int nt = (total - 1 - slot) / nwg + 1;           // tiles of this workgroup
+    const int S = nt * NI;                                 // its K steps, all tiles in a row
+    auto tile_of = [&](int j, int& tile_m, int& tile_n) {
+        const int pid = j * nwg + slot;
+        const int group_sz = kGroupM * tiles_n;
+        const int first_m = (pid / group_sz) * kGroupM;
+        const int gm = (tiles_m - first_m) < kGroupM ? (tiles_m - first_m) : kGroupM;
+        tile_m = first_m + (pid % group_sz) % gm;
+        tile_n = (pid % group_sz) / gm;
+    };
+
     // ---- LDS-DMA duty of this wave per step: three whole row tiles of codes (12 transfers of 1 KiB)
     // and one KiB of scale words (the words of four row tiles; wave 3 has only padding to move, which
-    // keeps the number of transfers per wave uniform for the waits below)
-    const uint8_t* dma_src[3];
+    // keeps the number of transfers per wave uniform for the waits below).  The transfers run two steps
+    // ahead of the MFMAs and carry on into the workgroup's next tile while the current one finishes.
+    const uint8_t* dma_src[3];                             // this lane's source of the step to transfer next
+    const uint8_t* sdma_src;
     uint32_t dma_dst[3];
     const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) const void*)lds);
 #pragma unroll
-    for (int k = 0; k < 3; ++k) {
-        const int tq = wave * 3 + k;                       // 0..3: A row tiles, 4..11: B row tiles
-        const uint8_t* base;
-        if (tq < kMT) {
-            int rt = tile_m * kMT + tq;
-            if (rt >= RTa) rt = RTa - 1;                   // ragged M: any valid tile, its rows are never stored
-            base = p.a_codes + rt * tile_bytes;
-        } else {
-            int rt = tile_n * kNT + (tq - kMT);
-            if (rt >= RTb) rt = RTb - 1;
-            base = p.b_codes + rt * tile_bytes;
+    for (int k = 0; k < 3; ++k) dma_dst[k] = lds0 + (wave * 3 + k) * kTileStepBytes;
+    const uint32_t sdma_dst = lds0 + kScalesOff + wave * 1024;
+    auto set_dma_tile = [&](int j) {
+        int tile_m, tile_n;
+        tile_of(j, tile_m, tile_n);
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            const int tq = wave * 3 + k;                   // 0..3: A row tiles, 4..11: B row tiles
+            const uint8_t* base;
+            if (tq < kMT) {
+                int rt = tile_m * kMT + tq;
+                if (rt >= RTa) rt = RTa - 1;               // ragged M: any valid tile, its rows are never stored
+                base = p.a_codes + rt * tile_bytes;
+            } else {
+                int rt = tile_n * kNT + (tq - kMT);
+                if (rt >= RTb) rt = RTb - 1;
+                base = p.b_codes + rt * tile_bytes;
+            }
+            dma_src[k] = base + lane * 16;
         }
-        dma_src[k] = base + lane * 16;
-        dma_dst[k] = lds0 + tq * kTileStepBytes;
-    }
-    // scale words: lane l of wave w moves 16 bytes = the words of lanes 4 (l % 16) .. + 3 of row tile
-    // 4 w + l / 16 (tiles 0..3: A, 4..11: B, 12..15: none -- wave 3 re-reads tile 11 into the padding)
-    const uint8_t* sdma_src;
-    {
+        // scale words: lane l of wave w moves 16 bytes = the words of lanes 4 (l % 16) .. + 3 of row tile
+        // 4 w + l / 16 (tiles 0..3: A, 4..11: B, 12..15: none -- wave 3 re-reads tile 11 into the padding)
         int tq = wave * 4 + (lane >> 4);
         if (tq > kMT + kNT - 1) tq = kMT + kNT - 1;
         const uint8_t* base;
@@ -208,14 +227,25 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
             base = p.b_scales + rt * tile_sbytes;
         }
         sdma_src = base + (lane & 15) * 16;
-    }
-    const uint32_t sdma_dst = lds0 + kScalesOff + wave * 1024;
+    };
+    int dma_j = 0, dma_it = 0;                             // tile and step within it that the sources point at
+    set_dma_tile(0);
+    auto advance_dma = [&]() {
+#pragma unroll
+        for (int k = 0; k < 3; ++k) dma_src[k] += kTileStepBytes;
+        sdma_src += 256;
+        if (++dma_it == NI) {
+            dma_it = 0;
+            if (++dma_j < nt) set_dma_tile(dma_j);
+        }
+    };
     constexpr int kDmaOps = 13;                            // transfers per wave per step
-    auto issue_dma = [&](int step, int stage) {
+    auto issue_dma = [&](int stage) {
         const uint32_t so = stage * kStageBytes;
 #pragma unroll
-        for (int k = 0; k < 3; ++k) dma_4k(dma_src[k] + (int64_t)step * kTileStepBytes, dma_dst[k] + so);
-        dma_1k(sdma_src + (int64_t)step * 256, sdma_dst + so);
+        for (int k = 0; k < 3; ++k) dma_4k(dma_src[k], dma_dst[k] + so);
+        dma_1k(sdma_src, sdma_dst + so);
+        advance_dma();
     };
 
     // ---- LDS read addresses: lane (r, g) reads group 4 g + i of row r at (4 g + i) * 512 + r * 16;
@@ -235,19 +265,11 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
         s.b[3] = *(const uint32_t*)(qb + 768);
     };
 
-    f32x16 acc[2][4];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
     // ---- prologue: the first two stages.  Transfers complete in issue order, so "at most 13
     // outstanding" means everything but the newest step's transfers has landed.
-    issue_dma(0, 0);
-    if (NI > 1) {
-        issue_dma(1, 1);
+    issue_dma(0);
+    if (S > 1) {
+        issue_dma(1);
         wait_vmcnt<kDmaOps>();
     } else {
         wait_vmcnt<0>();
@@ -259,8 +281,20 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
     read_scales(sc, 0);
     sn = sc;
 
-    // One K step.  MORE1 / MORE2: a next step / a step after that exists.
-    auto step = [&](int it, int stage, auto more1_c, auto more2_c) {
+    int stage = 0;                                         // stage of the step to compute next
+    for (int j = 0; j < nt; ++j) {                         // ---- one output tile per iteration
+    // The accumulators live and die inside one iteration: nothing but the transfer pipeline, the stage
+    // counter and the prefetched fragments of the next step is carried from tile to tile.
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][jj][e] = 0.f;
+
+    // One K step.  MORE1 / MORE2: a next step / a step after that exists (in this tile or the next).
+    auto step = [&](int stage, auto more1_c, auto more2_c) {
         constexpr bool MORE1 = decltype(more1_c)::value, MORE2 = decltype(more2_c)::value;
         const int stage1 = stage + 1 == kStages ? 0 : stage + 1;
         const int stage2 = stage1 + 1 == kStages ? 0 : stage1 + 1;
@@ -269,10 +303,10 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
         // every other MFMA: the CU's one texture path moves 64 B/clk, i.e. a step's 52 KiB take 832 of
         // the step's 1024 MFMA cycles, and a wave that issues its transfers in a burst sits behind the
         // other waves' bursts with its MFMAs waiting.
-        const uint8_t* d0 = dma_src[0] + (int64_t)(it + 2) * kTileStepBytes;
-        const uint8_t* d1 = dma_src[1] + (int64_t)(it + 2) * kTileStepBytes;
-        const uint8_t* d2 = dma_src[2] + (int64_t)(it + 2) * kTileStepBytes;
-        const uint8_t* d3 = sdma_src + (int64_t)(it + 2) * 256;
+        const uint8_t* d0 = dma_src[0];
+        const uint8_t* d1 = dma_src[1];
+        const uint8_t* d2 = dma_src[2];
+        const uint8_t* d3 = sdma_src;
         const uint32_t so2 = stage2 * kStageBytes;
         auto dma_slot = [&](auto kc) {
             constexpr int k = decltype(kc)::value;
@@ -313,6 +347,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
         DUQPP_QUARTER(2, f0, f1, 8, 9, 10, 11);
 #undef DUQPP_QUARTER
 #undef DUQPP_DMA
+        if constexpr (MORE2) advance_dma();
         if constexpr (MORE1) {
             // next stage landed for this wave, then for all; every LDS read of the current stage has
             // been issued and returns before any later transfer can touch it
@@ -335,72 +370,88 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
 #undef DUQPP_PIN
         sc = sn;
     };
-    int it = 0, stage = 0;
-    for (; it + 2 < NI; ++it) {
-        step(it, stage, std::true_type{}, std::true_type{});
-        stage = stage + 1 == kStages ? 0 : stage + 1;
-    }
-    if (it + 1 < NI) {
-        step(it, stage, std::true_type{}, std::false_type{});
-        stage = stage + 1 == kStages ? 0 : stage + 1;
-        ++it;
-    }
-    step(it, stage, std::false_type{}, std::false_type{});
 
-    // ---- epilogue: acc[i][j][e] of lane (r, g) is row 32 i + 8 (e / 4) + 4 g + e % 4, column 32 j + r
-    const int m0 = tile_m * kBM + wm * 64, n0 = tile_n * kBN + wn * 128;
-    if constexpr (OUT_BF16) {
-        // A direct store would write 2 bytes per lane, 64 contiguous bytes per instruction and row.
-        // Instead the wave's 64 x 128 tile is transposed through LDS (free once every wave is past the
-        // K loop) and leaves as 16-byte pieces, 256 contiguous bytes per row.  Rows are padded to 272
-        // bytes so that the two half-waves (four rows apart) fall on different banks.
-        const bool vec_ok = ((reinterpret_cast<uintptr_t>(p.y) & 15) == 0) && (p.ldy % 8) == 0;
-        if (vec_ok) {
-            constexpr int kRowPitch = 272;
-            workgroup_barrier();                           // all waves have read their last fragments
-            uint8_t* ep = lds + wave * (64 * kRowPitch);
+    // ---- a finished tile: acc[i][j][e] of lane (r, g) is row 32 i + 8 (e / 4) + 4 g + e % 4, column 32 j + r.
+    // `stage` is the stage the tile's last step consumed: no wave reads it any more (`synced`: they have all
+    // passed a barrier since), and the only transfers that will write bytes [12288 w, 12288 (w + 1)) of it are
+    // wave w's own, issued later in program order -- so that range is wave w's scratch for the bf16 transpose.
+    auto store_tile = [&](int j, int stage, bool synced) {
+        int tile_m, tile_n;
+        tile_of(j, tile_m, tile_n);
+        const int m0 = tile_m * kBM + wm * 64, n0 = tile_n * kBN + wn * 128;
+        if constexpr (OUT_BF16) {
+            // A direct store would write 2 bytes per lane, 64 contiguous bytes per instruction and row.
+            // Instead each 32 x 128 half of the wave's tile is transposed through LDS and leaves as 16-byte
+            // pieces, 256 contiguous bytes per row.  Rows are padded to 272 bytes so that the two
+            // half-waves (four rows apart) fall on different banks.
+            const bool vec_ok = ((reinterpret_cast<uintptr_t>(p.y) & 15) == 0) && (p.ldy % 8) == 0;
+            if (vec_ok) {
+                constexpr int kRowPitch = 272;
+                static_assert(32 * kRowPitch <= 3 * kTileStepBytes, "scratch within the wave's own transfer range");
+                if (!synced) workgroup_barrier();
+                uint8_t* ep = lds + stage * kStageBytes + wave * (3 * kTileStepBytes);
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+                for (int i = 0; i < 2; ++i) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                    for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int row = 32 * i + 8 * (e / 4) + 4 * g + (e % 4);
-                        *(uint16_t*)(ep + row * kRowPitch + (32 * j + r) * 2) = f32_to_bf16_rne(acc[i][j][e]);
+                        for (int e = 0; e < 16; ++e) {
+                            const int row = 8 * (e / 4) + 4 * g + (e % 4);
+                            *(uint16_t*)(ep + row * kRowPitch + (32 * jj + r) * 2) = f32_to_bf16_rne(acc[i][jj][e]);
+                        }
+                    // same wave wrote and reads: program order suffices within a wave
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const int row = k * 4 + (lane >> 4), ch = lane & 15;
+                        const int grow = m0 + 32 * i + row, gcol = n0 + ch * 8;
+                        const u32x4 v = *(const u32x4*)(ep + row * kRowPitch + ch * 16);
+                        if (grow < p.T && gcol < p.N) {
+                            uint16_t* dst = (uint16_t*)p.y + (int64_t)grow * p.ldy + gcol;
+                            if (gcol + 8 <= p.N) {
+                                *(u32x4*)dst = v;
+                            } else {                       // ragged right edge
+                                for (int c = 0; c < 8 && gcol + c < p.N; ++c) dst[c] = (uint16_t)(v[c / 2] >> (16 * (c & 1)));
+                            }
+                        }
                     }
-            // same wave wrote and reads: program order suffices within a wave
+                }
+                return;
+            }
+        }
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                const int row = k * 4 + (lane >> 4), ch = lane & 15;
-                const int grow = m0 + row, gcol = n0 + ch * 8;
-                if (grow < p.T && gcol < p.N) {
-                    const u32x4 v = *(const u32x4*)(ep + row * kRowPitch + ch * 16);
-                    uint16_t* dst = (uint16_t*)p.y + (int64_t)grow * p.ldy + gcol;
-                    if (gcol + 8 <= p.N) {
-                        *(u32x4*)dst = v;
-                    } else {                               // ragged right edge
-                        for (int c = 0; c < 8 && gcol + c < p.N; ++c) dst[c] = (uint16_t)(v[c / 2] >> (16 * (c & 1)));
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int col = n0 + 32 * jj + r;
+                if (col >= p.N) continue;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = m0 + 32 * i + 8 * (e / 4) + 4 * g + (e % 4);
+                    if (row < p.T) {
+                        if (OUT_BF16) ((uint16_t*)p.y)[(int64_t)row * p.ldy + col] = f32_to_bf16_rne(acc[i][jj][e]);
+                        else ((float*)p.y)[(int64_t)row * p.ldy + col] = acc[i][jj][e];
                     }
                 }
             }
-            return;
-        }
+    };
+
+    // Steps of this tile.  All but the last two steps of the whole run have two successors.
+    const int s0 = j * NI;
+    int hot = S - 2 - s0;
+    hot = hot < 0 ? 0 : (hot > NI ? NI : hot);
+    int it = 0;
+    for (; it < hot; ++it) {
+        step(stage, std::true_type{}, std::true_type{});
+        stage = stage + 1 == kStages ? 0 : stage + 1;
     }
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int col = n0 + 32 * j + r;
-            if (col >= p.N) continue;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int row = m0 + 32 * i + 8 * (e / 4) + 4 * g + (e % 4);
-                if (row < p.T) {
-                    if (OUT_BF16) ((uint16_t*)p.y)[(int64_t)row * p.ldy + col] = f32_to_bf16_rne(acc[i][j][e]);
-                    else ((float*)p.y)[(int64_t)row * p.ldy + col] = acc[i][j][e];
-                }
-            }
-        }
+    for (; it < NI; ++it) {
+        if (s0 + it + 1 < S) step(stage, std::true_type{}, std::false_type{});
+        else step(stage, std::false_type{}, std::false_type{});
+        stage = stage + 1 == kStages ? 0 : stage + 1;
+    }
+    // a step with a successor ends behind a barrier
+    store_tile(j, stage == 0 ? kStages - 1 : stage - 1, s0 + NI < S);
+    }                                                      // ---- tile loop
 }
 
 hipError_t launch_gemm_tiled(const TiledGemmParams& p, hipStream_t stream) {
@@ -416,7 +467,10 @@ hipError_t launch_gemm_tiled(const TiledGemmParams& p, hipStream_t stream) {
         configured.store(1, std::memory_order_release);
     }
     const int tiles_m = (p.T + kBM - 1) / kBM, tiles_n = (p.N + kBN - 1) / kBN;
-    dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
+    // persistent workgroups: the 156 KiB of LDS allow one per CU, and each walks its tiles with the
+    // transfer pipeline running across tile boundaries
+    const int total = tiles_m * tiles_n;
+    dim3 grid((unsigned)(total < kNumCU ? total : kNumCU)), block(256);
     if (p.out_bf16) hipLaunchKernelGGL(gemm_tiled_kernel<true>, grid, block, kGemmLdsBytes, stream, p);
     else hipLaunchKernelGGL(gemm_tiled_kernel<false>, grid, block, kGemmLdsBytes, stream, p);
     return hipGetLastError();
