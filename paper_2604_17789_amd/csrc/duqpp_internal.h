@@ -30,9 +30,10 @@ struct RotqParams {
     int ngroups;         // ceil(ntiles / tiles_per_wg)
     int nchunks;         // column chunks (each covers waves*2 blocks)
     int waves;           // wavefronts per workgroup
+    int by_columns;      // tiled-output kernel: an XCD owns column chunks (1) or token runs (0)
 };
 hipError_t launch_rotq(const RotqParams& p, hipStream_t stream);
-void plan_rotq(RotqParams& p);    // fills ntiles / tiles_per_wg / ngroups / nchunks / waves
+void plan_rotq(RotqParams& p);    // fills ntiles / tiles_per_wg / ngroups / nchunks / waves / by_columns
 
 struct QuantDbgParams {
     const float* y; int64_t ldy; int rows; int G; uint8_t* codes; uint8_t* scales;

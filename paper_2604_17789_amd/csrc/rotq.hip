@@ -398,12 +398,15 @@ __global__ __launch_bounds__(512) void rotq_wave_kernel(RotqParams p) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     int logical;
     logical_workgroup(logical);
-    // Consecutive workgroups (which the renumbering keeps on one XCD) take consecutive column chunks of
-    // the same token rows: together they read whole rows of X, and their addresses spread over all L2
-    // channels -- workgroups that share a column chunk sit at the same offset in every row, and a row
-    // length that is a multiple of the channel interleave then sends them all to the same few channels.
-    const int chunk = logical % p.nchunks;
-    const int tg = logical / p.nchunks;
+    // Which workgroups share an XCD (the renumbering keeps consecutive logical ones together):
+    //  - by_columns: an XCD owns a few column chunks for all token runs, so each rotation block is fetched
+    //    into one L2 only.  Its workgroups sit at a few fixed offsets within every row of X, and a row length
+    //    that is a multiple of the L2 channel interleave sends them all to the same channels -- harmless
+    //    only when an XCD owns enough chunks (>= 3 KiB of a row) to spread over the channels;
+    //  - otherwise consecutive workgroups take consecutive chunks of the same token rows: together they
+    //    read whole rows, every channel is used, and every XCD fetches every rotation block.
+    const int chunk = p.by_columns ? logical / p.ngroups : logical % p.nchunks;
+    const int tg = p.by_columns ? logical % p.ngroups : logical / p.nchunks;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 31, h = lane >> 5;
@@ -477,6 +480,7 @@ void plan_rotq(RotqParams& p) {
         p.waves = 8;
         while (p.waves > 1 && (int64_t)((npairs + p.waves - 1) / p.waves) * p.ntiles < kNumCU) p.waves /= 2;
         p.nchunks = (npairs + p.waves - 1) / p.waves;
+        p.by_columns = p.nchunks >= 3 * kNumXCD;
     } else {
         p.waves = kRotqWaves;
         p.nchunks = (p.G + kBlocksPerWG - 1) / kBlocksPerWG;

@@ -84,6 +84,26 @@ def test_rotate_quantize_tiled(env, T, K):
     assert rotation_error_ratio(yrot.cpu().numpy(), rotation.rotate(xf, R), xf) <= 1e-5
 
 
+def test_rotate_quantize_tiled_shared_block(env):
+    """One rotation block shared by every group (the deployed variant of Sec. 4.2): same result as the
+    row-major kernel, which is held to the oracle, and as K/32 copies of the block."""
+    torch, duqpp = env
+    T, K = 200, 2048
+    xb = wl.make_activations("gpu-rqt-shared", T, K, (wl.OutlierSpec(8, 50.0),))
+    R1 = wl.make_rotation_blocks("gpu-rqt-shared", 1)
+    x = to_dev_bf16(xb, torch)
+    ct, st = duqpp.rotate_quantize_tiled(x, to_dev(R1, torch))
+    c_rm, s_rm = duqpp.rotate_quantize(x, to_dev(R1, torch))
+    ct2, st2 = duqpp.rotate_quantize_tiled(x, to_dev(np.repeat(R1, K // 32, axis=0), torch))
+    torch.cuda.synchronize()
+    codes, scales, _, _ = untile_np(ct.cpu().numpy(), st.cpu().numpy(), T, K)
+    np.testing.assert_array_equal(codes, c_rm.cpu().numpy())
+    np.testing.assert_array_equal(scales, s_rm.cpu().numpy())
+    assert torch.equal(ct, ct2) and torch.equal(st, st2)
+    c_ref, s_ref, _ = pipeline.rotate_quantize(xb, R1)
+    assert np.mean(codes != c_ref) < 1e-4                  # each side rotates in its own precision
+
+
 def test_quantize_weights_tiled(env):
     torch, duqpp = env
     N, K = 200, 1184
