@@ -44,7 +44,7 @@ constexpr int kTileStepBytes = 8 * 512;                 // one row tile, one K s
 constexpr int kStageBytes = (kMT + kNT) * kTileStepBytes + 4 * 1024;   // codes + scale words
 constexpr int kStages = 3;
 constexpr int kGemmLdsBytes = kStages * kStageBytes;    // 159744 of the CU's 163840
-constexpr int kGroupM = 4;                              // M tiles per group in the workgroup ordering
+constexpr int kGroupM = 8;                              // M tiles per group in the workgroup ordering: an XCD's 32 workgroups form an 8 x 4 block (1024 x 1024 outputs), the shape with the fewest operand rows
 
 constexpr int kScaleRegionBytes = 4 * 1024;               // 12 x 256 B of scale words + 1 KiB of padding
 constexpr int kScalesOff = (kMT + kNT) * kTileStepBytes;  // scale words follow the codes in a stage
