@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--sets", type=int, default=8, help="distinct buffer sets the batches rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="time eager launches only (no HIP graph capture)")
+    ap.add_argument("--zero-operands", action="store_true",
+                    help="diagnostic, not the metric: time the GEMM on all-zero codes (weights and activations), "
+                         "which takes the data-dependent power draw of the matrix cores out of the measurement")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the workload, run a plain device copy of known size (256 MiB, 20 times): "
                          "the reference against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -120,6 +123,13 @@ def main():
     # the timed path: activations rotated + quantised into the tiled operand layout, then the tiled GEMM
     def rotq1(l):
         duqpp.rotate_quantize_tiled(l["x"], l["R"], out=(l["ac"], l["asc"]))
+
+    if args.zero_operands:
+        for s_ in sets:
+            for l in s_:
+                l["bc"].zero_()
+                l["x"].zero_()
+        torch.cuda.synchronize()
 
     def gemm1(l):
         duqpp.mxfp4_gemm_tiled(l["ac"], l["asc"], l["bc"], l["bs"], T, l["N"], l["K"], out_dtype=out_dtype, out=l["y"])
@@ -217,7 +227,7 @@ def main():
         "launch": "HIP graph replay of the timed steps" if whole["graph"] else "eager launches",
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "mxfp4 (E2M1 codes + E8M0 scales; fp32 rotation and accumulation)",
-        "data": "synthetic",
+        "data": "synthetic" if not args.zero_operands else "all-zero operands (diagnostic run, not the metric)",
         "config": {"workload": args.config, "T": T,
                    "linears": [{"name": nm, "K": k, "N": n} for nm, k, n, _ in linears],
                    "output": cfg["out"], "buffer_sets": nsets, "operand_layout": "tiled"},
@@ -257,7 +267,9 @@ def main():
             threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             threads = os.cpu_count() or 1
-        Ts = min(T, 256)
+        # a bounded sample: every token (at most 8192) of one linear -- 2 to 10 s of oracle work at the
+        # benchmark shapes, most of it the fp64 product
+        Ts = min(T, 8192)
         s0 = sets[0][-1]
         bc_rm, bs_rm = duqpp.untile_operand(s0["bc"], s0["bs"], N, K)       # row-major view of the weights for the oracle
         bc_h, bs_h = bc_rm.cpu().numpy(), bs_rm.cpu().numpy()
