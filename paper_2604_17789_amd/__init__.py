@@ -5,6 +5,8 @@ kernels; this module only marshals torch device tensors into raw pointers and si
 There is no CPU or PyTorch fallback: importing without the built library raises.
 """
 from .binding import (  # noqa: F401
+    BF16,
+    F32,
     DuqppError,
     gemm_workspace_bytes,
     lib,
