@@ -455,7 +455,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
 }
 
 hipError_t launch_gemm_tiled(const TiledGemmParams& p, hipStream_t stream) {
-    if (p.T <= 32) return launch_gemm_decode(p, stream);    // weight-streaming shape
+    if (p.T <= kDecodeMaxT) return launch_gemm_decode(p, stream);    // weight-streaming shape
     static std::atomic<int> configured{0};
     if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)gemm_tiled_kernel<true>,

@@ -137,6 +137,9 @@ GEMM_SHAPES = [
     (16, 300, 2048),
     (24, 200, 1184),      # one ragged row tile, ragged K steps over the decode kernel's eight waves
     (32, 96, 32),         # decode kernel, a single group
+    (33, 200, 1184),      # decode kernel with two activation row tiles, the second almost empty
+    (64, 4100, 288),      # two full activation row tiles, 129 weight row tiles (each cut in two)
+    (50, 8200, 544),      # two activation row tiles, 257 weight row tiles (whole tiles per workgroup)
     (130, 70, 32),        # a single group (one K step of mostly padding)
     (200, 264, 2304),
     (129, 513, 1312),
