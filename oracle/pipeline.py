@@ -3,10 +3,11 @@
     rotate_quantize   X^ = X . R^ , then Eq. 2            (online, activations)
     quantize_weights  W^ = R^T W  , then Eq. 2            (offline, weights stored [N, K])
     rotq_gemm         Q(X . R^) . Q(W^)                   (fused form: same codes, same product)
+With `lam` (the diagonal of Eq. 3) the operands are X Lambda^-1 R^ and R^T Lambda W, as Eq. 5 is written.
 """
 import numpy as np
 
-from . import linear, mxfp4, rotation
+from . import linear, mxfp4, rotation, smoothing
 
 
 def _as_real(x):
@@ -17,16 +18,24 @@ def _as_real(x):
     return x
 
 
-def rotate_quantize(x, R):
+def rotate_quantize(x, R, lam=None):
     """Returns (codes, scales, y_rot fp32)."""
-    y = rotation.rotate(_as_real(x), R)
+    x = _as_real(x)
+    if lam is not None:
+        x = smoothing.apply(x, lam, inverse=True)
+    y = rotation.rotate(x, R)
     codes, scales = mxfp4.quantize(y)
     return codes, scales, y
 
 
-def quantize_weights(w, R):
-    """w [N, K]: each row rotated like a token, then quantised along K."""
-    return rotate_quantize(w, R)
+def quantize_weights(w, R, lam=None):
+    """w [N, K]: each row (scaled by Lambda when given) rotated like a token, then quantised along K."""
+    w = _as_real(w)
+    if lam is not None:
+        w = smoothing.apply(w, lam, inverse=False)
+    y = rotation.rotate(w, R)
+    codes, scales = mxfp4.quantize(y)
+    return codes, scales, y
 
 
 def rotq_gemm(x, R, b_codes, b_scales):
