@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--sets", type=int, default=8, help="distinct buffer sets the batches rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="time eager launches only (no HIP graph capture)")
+    ap.add_argument("--smoothing", action="store_true",
+                    help="run the smoothed form of the path (Eq. 5 as written): a synthetic smoothing diagonal is "
+                         "merged into the rotation blocks offline; the timed kernels are the same")
     ap.add_argument("--zero-operands", action="store_true",
                     help="diagnostic, not the metric: time the GEMM on all-zero codes (weights and activations), "
                          "which takes the data-dependent power draw of the matrix cores out of the measurement")
@@ -98,6 +101,7 @@ def main():
     sets = []
     x0_bits = None
     R0 = None
+    lam0 = None
     for s in range(nsets):
         layers = []
         for nm, k, n, outl in linears:
@@ -105,11 +109,15 @@ def main():
             xb = wl.make_activations(tag, T, k, outl)
             wb = wl.make_weights(tag, n, k, cfg["w_std"])
             R = wl.make_rotation_blocks(tag, k // 32)
+            lam = wl.make_smoothing_scales(tag, k) if args.smoothing else None
             if s == 0 and nm == linears[-1][0]:
-                x0_bits, R0 = xb, R
+                x0_bits, R0, lam0 = xb, R, lam
             x, Rd = dev_bf16(xb), torch.from_numpy(R).to(dev)
             w = dev_bf16(wb)
-            bc, bs = duqpp.quantize_weights_tiled(w, Rd)  # offline weight transform (tiled layout), not timed
+            Rw = Rd
+            if args.smoothing:                            # offline: diag(1/lambda) R for X, diag(lambda) R for W
+                Rd, Rw = duqpp.fold_smoothing(Rd, torch.from_numpy(lam).to(dev))
+            bc, bs = duqpp.quantize_weights_tiled(w, Rw)  # offline weight transform (tiled layout), not timed
             del w, wb, xb
             cb, sb = duqpp.tiled_bytes(T, k)
             layers.append(dict(
@@ -230,7 +238,8 @@ def main():
         "data": "synthetic" if not args.zero_operands else "all-zero operands (diagnostic run, not the metric)",
         "config": {"workload": args.config, "T": T,
                    "linears": [{"name": nm, "K": k, "N": n} for nm, k, n, _ in linears],
-                   "output": cfg["out"], "buffer_sets": nsets, "operand_layout": "tiled"},
+                   "output": cfg["out"], "buffer_sets": nsets, "operand_layout": "tiled",
+                   "smoothing": bool(args.smoothing)},
         "components": {
             "rotate_quantize": {"us": round(rotq_us, 2), "us_eager_launches": round(rotq_eager_us, 2),
                                 "launches": len(linears), "GB/s": round(rotq_gbps, 1),
@@ -274,7 +283,7 @@ def main():
         bc_rm, bs_rm = duqpp.untile_operand(s0["bc"], s0["bs"], N, K)       # row-major view of the weights for the oracle
         bc_h, bs_h = bc_rm.cpu().numpy(), bs_rm.cpu().numpy()
         c0 = time.perf_counter()
-        a_codes, a_scales, _ = oracle.pipeline.rotate_quantize(x0_bits[:Ts], R0)
+        a_codes, a_scales, _ = oracle.pipeline.rotate_quantize(x0_bits[:Ts], R0, lam=lam0)
         y_ref = oracle.linear.mxfp4_gemm(a_codes, a_scales, bc_h, bs_h)
         c1 = time.perf_counter()
         result["cpu_baseline"] = {

@@ -9,7 +9,8 @@
  * groups (Eq. 4, B = 32) and Q is MXFP4 quantisation (Sec. 3.2, Eq. 2): every 32
  * consecutive values along the reduction axis K share one E8M0 power-of-two scale
  * 2^(floor(log2 amax) - 2) and are stored as 4-bit E2M1 codes (round to nearest, ties to
- * even, saturating at +-6).  The smoothing diagonal of Eq. 3 is not applied on this path.
+ * even, saturating at +-6).  The smoothing diagonal of Eq. 3 enters through the rotation blocks
+ * (duqpp_fold_smoothing); the kernels take any 32x32 fp32 blocks, orthogonal or not.
  *
  * Conventions (all entry points)
  *   - Every pointer is a DEVICE pointer unless its comment says "host".  The caller owns
@@ -171,6 +172,20 @@ int duqpp_rotq_gemm_tiled(const void* x_bf16, int64_t ldx, const float* R, int64
                           int64_t T, int64_t N, int64_t K,
                           void* y, int out_dtype, int64_t ldy,
                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Smoothing (Sec. 4.2, Eq. 3) merged into the rotation blocks, offline.  Eq. 5 in full is
+ * Y = Q(X Lambda^-1 R^) . Q(R^T Lambda W) with a diagonal Lambda over the reduction axis.  A diagonal times a
+ * block-diagonal matrix is block-diagonal, so with
+ *     R_act[j][r][c] = R[j][r][c] / lambda[32 j + r],      R_wgt[j][r][c] = R[j][r][c] * lambda[32 j + r]
+ * duqpp_rotate_quantize(x, R_act) produces Q(X Lambda^-1 R^) and duqpp_quantize_weights(w, R_wgt) produces
+ * Q(R^T Lambda W): the online path is unchanged and costs nothing extra.
+ *   R       in   [n_rblocks, 32, 32] fp32, n_rblocks == K/32 or 1 (a shared block expands to K/32 blocks)
+ *   lambda  in   [K] fp32, finite and positive (not checked: it lives on the device)
+ *   R_act, R_wgt  out  [K/32, 32, 32] fp32 each; must not alias R
+ */
+int duqpp_fold_smoothing(const float* R, int64_t n_rblocks, const float* lambda, int64_t K,
+                         float* R_act, float* R_wgt, void* stream);
 
 /* Host, pure: scratch bytes duqpp_mxfp4_gemm (fused = 0) can use or duqpp_rotq_gemm (fused = 1) needs:
  * room for both operands in the tiled layout.  0 for invalid shapes. */

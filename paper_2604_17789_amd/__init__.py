@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     BF16,
     F32,
     DuqppError,
+    fold_smoothing,
     gemm_workspace_bytes,
     lib,
     library_path,

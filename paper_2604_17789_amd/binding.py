@@ -46,8 +46,10 @@ def _load():
     L.duqpp_rotate_quantize_tiled.argtypes = [vp, i64, i64, i64, fp, i64, u8p, u8p, vp]
     L.duqpp_mxfp4_gemm_tiled.argtypes = [u8p, u8p, u8p, u8p, i64, i64, i64, vp, ci, i64, vp]
     L.duqpp_rotq_gemm_tiled.argtypes = [vp, i64, fp, i64, u8p, u8p, i64, i64, i64, vp, ci, i64, vp, sz, vp]
+    L.duqpp_fold_smoothing.argtypes = [fp, i64, fp, i64, fp, fp, vp]
     for name in ("duqpp_tiled_bytes", "duqpp_tile_operand", "duqpp_untile_operand", "duqpp_quantize_weights_tiled",
-                 "duqpp_rotate_quantize_tiled", "duqpp_mxfp4_gemm_tiled", "duqpp_rotq_gemm_tiled"):
+                 "duqpp_rotate_quantize_tiled", "duqpp_mxfp4_gemm_tiled", "duqpp_rotq_gemm_tiled",
+                 "duqpp_fold_smoothing"):
         getattr(L, name).restype = ci
     for name in ("duqpp_quantize_weights", "duqpp_rotate_quantize", "duqpp_mxfp4_gemm", "duqpp_rotq_gemm",
                  "duqpp_quantize_f32_dbg", "duqpp_validate_rotate_quantize", "duqpp_validate_mxfp4_gemm"):
@@ -299,3 +301,18 @@ def rotq_gemm_tiled(x, R, b_codes_t, b_scales_t, N, out_dtype=F32, out=None, wor
                                      b_scales_t.data_ptr(), T, N, K, y.data_ptr(), out_dtype, y.stride(0),
                                      workspace.data_ptr(), workspace.numel(), _stream()), "duqpp_rotq_gemm_tiled")
     return y
+
+
+def fold_smoothing(R, lam):
+    """R fp32 [K/32 or 1, 32, 32], lam fp32 [K] (the diagonal of the smoothing step) -> (R_act, R_wgt), fp32
+    [K/32, 32, 32] each: rotate_quantize(x, R_act) and quantize_weights(w, R_wgt) then yield the smoothed operands."""
+    _dev(R, torch.float32, "R")
+    _dev(lam, torch.float32, "lam")
+    if lam.dim() != 1 or not lam.is_contiguous():
+        raise ValueError("lam must be a contiguous vector of K entries")
+    K = lam.shape[0]
+    R_act = torch.empty((K // 32, 32, 32), dtype=torch.float32, device=R.device)
+    R_wgt = torch.empty_like(R_act)
+    _check(lib.duqpp_fold_smoothing(R.data_ptr(), _n_rblocks(R), lam.data_ptr(), K, R_act.data_ptr(),
+                                    R_wgt.data_ptr(), _stream()), "duqpp_fold_smoothing")
+    return R_act, R_wgt

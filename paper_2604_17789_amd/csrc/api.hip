@@ -271,6 +271,19 @@ int duqpp_rotq_gemm_tiled(const void* x_bf16, int64_t ldx, const float* R, int64
     return duqpp_mxfp4_gemm_tiled(a_codes, a_scales, b_codes_t, b_scales_t, T, N, K, y, out_dtype, ldy, stream);
 }
 
+int duqpp_fold_smoothing(const float* R, int64_t n_rblocks, const float* lambda, int64_t K, float* R_act,
+                         float* R_wgt, void* stream) {
+    if (!R || !lambda || !R_act || !R_wgt) return DUQPP_ERR_NULL;
+    if (K < 32 || (K % 32) != 0 || K > (int64_t)1 << 30) return DUQPP_ERR_SHAPE;
+    if (n_rblocks != 1 && n_rblocks != K / 32) return DUQPP_ERR_SHAPE;
+    if (!aligned_to(R, 4) || !aligned_to(lambda, 4) || !aligned_to(R_act, 4) || !aligned_to(R_wgt, 4))
+        return DUQPP_ERR_ALIGN;
+    int st = check_device();
+    if (st != DUQPP_OK) return st;
+    FoldParams p{R, n_rblocks == 1 ? 0 : 1024, lambda, R_act, R_wgt, (int)(K / 32)};
+    return launch_fold_smoothing(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
+}
+
 const char* duqpp_status_string(int status) {
     switch (status) {
         case DUQPP_OK: return "ok";

@@ -74,6 +74,15 @@ struct LayoutParams {
 hipError_t launch_tile(const LayoutParams& p, hipStream_t stream);     // row-major -> tiled (writes the padding too)
 hipError_t launch_untile(const LayoutParams& p, hipStream_t stream);   // tiled -> row-major
 
+// ---- smoothing merged into the rotation blocks (smooth.hip) ---------------------------------
+struct FoldParams {
+    const float* R; int r_stride;      // [G or 1][32][32]; floats between blocks (0 when shared)
+    const float* lambda;               // [32 G]
+    float* R_act; float* R_wgt;        // [G][32][32] each
+    int G;
+};
+hipError_t launch_fold_smoothing(const FoldParams& p, hipStream_t stream);
+
 struct TiledGemmParams {
     const uint8_t* a_codes; const uint8_t* a_scales;   // tiled, T rows
     const uint8_t* b_codes; const uint8_t* b_scales;   // tiled, N rows

@@ -92,6 +92,10 @@ def test_entry_points_reject_bad_arguments_before_any_launch(lib):
     assert lib.duqpp_mxfp4_gemm(P, P, P, P, 8, 16, 64, P, 9, 16, None, 0, None) == DTYPE
     assert lib.duqpp_rotq_gemm(P, 64, P, 2, P, P, 8, 16, 64, P, 0, 16, None, 0, None) == WORKSPACE
     assert lib.duqpp_quantize_f32_dbg(None, 4, 64, 64, P, P, None) == NULL
+    assert lib.duqpp_fold_smoothing(P, 2, None, 64, P, P, None) == NULL
+    assert lib.duqpp_fold_smoothing(P, 3, P, 64, P, P, None) == SHAPE      # n_rblocks not in {1, K/32}
+    assert lib.duqpp_fold_smoothing(P, 2, P, 48, P, P, None) == SHAPE
+    assert lib.duqpp_fold_smoothing(P, 2, P + 2, 64, P, P, None) == ALIGN
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

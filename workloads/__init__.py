@@ -16,6 +16,7 @@ from .generators import (  # noqa: F401
     identity_blocks,
     make_activations,
     make_rotation_blocks,
+    make_smoothing_scales,
     make_weights,
     stream_seed,
 )

@@ -102,6 +102,13 @@ def make_rotation_blocks(name: str, G: int) -> np.ndarray:
     return np.ascontiguousarray(q.astype(np.float32))
 
 
+def make_smoothing_scales(name: str, K: int, spread: float = 2.0) -> np.ndarray:
+    """A synthetic smoothing diagonal [K] fp32: log-uniform in [2^-spread, 2^spread].  Stands in for scales
+    calibrated on real activations and weights, which are not available."""
+    rng = _rng(name, "lambda", K)
+    return np.exp2(rng.uniform(-spread, spread, size=K)).astype(np.float32)
+
+
 def identity_blocks(G: int) -> np.ndarray:
     return np.ascontiguousarray(np.broadcast_to(np.eye(BLOCK, dtype=np.float32), (G, BLOCK, BLOCK)))
 
