@@ -1,6 +1,6 @@
-// Decode-shape W4A4 MXFP4 GEMM (Eq. 5 with a handful of tokens): T <= 64, so the activations are one or
-// two row tiles (MT) and the product is bound by streaming the weights once from HBM (N * K * 17/32
-// bytes).  Tiled operand layout, same instruction and K permutation as the prefill kernel.
+// Decode-shape W4A4 MXFP4 GEMM (Eq. 5 with a handful of tokens): T <= 128, so the activations are one to
+// four row tiles (MT = 1 or 2 per workgroup, one or two passes over the weights along blockIdx.y) and the
+// product is bound by streaming the weights from HBM (N * K * 17/32 bytes).  Tiled operand layout, same instruction and K permutation as the prefill kernel.
 //
 // One workgroup of 8 waves per ROWS = 32 or 16 output channels of a weight row tile: the streaming rate
 // a single CU sustains is a small fraction of the chip's, so the launch wants at least one workgroup per
@@ -38,16 +38,17 @@ struct DecStep {
 // a_tile_bytes / a_tile_sbytes: distance between the activations' row tiles (codes / scale words)
 template <int ROWS, int MT>
 __device__ __forceinline__ void dec_load(DecStep<MT>& d, const uint8_t* a_codes, const uint8_t* a_scales,
-                                         int64_t a_tile_bytes, int64_t a_tile_sbytes,
+                                         int64_t a_tile_bytes, int64_t a_tile_sbytes, int m0, int rta,
                                          const uint8_t* b_codes, const uint8_t* b_scales, int step, int lane_code,
                                          int lane4, int lane_code_b, int lane4_b, int r) {
     const uint8_t* pb = b_codes + (int64_t)step * 4096 + lane_code_b;
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
-        const uint8_t* pa = a_codes + m * a_tile_bytes + (int64_t)step * 4096 + lane_code;
+        const int mt = m0 + m < rta ? m0 + m : rta - 1;
+        const uint8_t* pa = a_codes + mt * a_tile_bytes + (int64_t)step * 4096 + lane_code;
 #pragma unroll
         for (int i = 0; i < 4; ++i) d.a[m][i] = *(const u32x4*)(pa + i * 512);
-        d.sa[m] = *(const uint32_t*)(a_scales + m * a_tile_sbytes + (int64_t)step * 256 + lane4);
+        d.sa[m] = *(const uint32_t*)(a_scales + mt * a_tile_sbytes + (int64_t)step * 256 + lane4);
     }
     // weights are read once; lanes beyond the workgroup's rows load nothing and feed zeros
     if (ROWS == 32 || r < ROWS) {
@@ -86,6 +87,10 @@ __global__ __launch_bounds__(kDecWaves * 64) void gemm_decode_kernel(TiledGemmPa
     const uint8_t* b_codes = p.b_codes + (int64_t)rt * p.GP * 512;
     const uint8_t* b_scales = p.b_scales + (int64_t)rt * NI * 256;
     const int64_t a_tile_bytes = (int64_t)p.GP * 512, a_tile_sbytes = (int64_t)NI * 256;
+    // this workgroup's activation row tiles: MT of them from m0; one past the last tile is replaced by the
+    // last tile (its results fall on tokens >= T and are dropped)
+    const int RTa = (p.T + 31) / 32;
+    const int m0 = blockIdx.y * MT;
     // A operand (activations): group 4 g + i of row r sits at (4 g + i) * 512 + r * 16, its scale word at
     // (32 g + r) * 4; B operand (weights): the same with row rb
     const int lane_code = g * 2048 + r * 16, lane_code_b = g * 2048 + rb * 16;
@@ -101,11 +106,11 @@ __global__ __launch_bounds__(kDecWaves * 64) void gemm_decode_kernel(TiledGemmPa
     // (Deeper register rings measured slower: they cost the occupancy that hides the latency better.)
     DecStep<MT> cur, nxt;
     if (s0 < s1)
-        dec_load<ROWS, MT>(cur, p.a_codes, p.a_scales, a_tile_bytes, a_tile_sbytes, b_codes, b_scales, s0, lane_code,
+        dec_load<ROWS, MT>(cur, p.a_codes, p.a_scales, a_tile_bytes, a_tile_sbytes, m0, RTa, b_codes, b_scales, s0, lane_code,
                            lane4, lane_code_b, lane4_b, r);
     for (int s = s0; s < s1; ++s) {
         if (s + 1 < s1)
-            dec_load<ROWS, MT>(nxt, p.a_codes, p.a_scales, a_tile_bytes, a_tile_sbytes, b_codes, b_scales, s + 1,
+            dec_load<ROWS, MT>(nxt, p.a_codes, p.a_scales, a_tile_bytes, a_tile_sbytes, m0, RTa, b_codes, b_scales, s + 1,
                                lane_code, lane4, lane_code_b, lane4_b, r);
 #pragma unroll
         for (int m = 0; m < MT; ++m) {
@@ -123,7 +128,7 @@ __global__ __launch_bounds__(kDecWaves * 64) void gemm_decode_kernel(TiledGemmPa
 #pragma unroll
         for (int e = 0; e < 16; ++e) part[wave][e][lane] = acc[m][e];
         __syncthreads();
-        // acc[e] of lane (r, g): token 32 m + 8 (e / 4) + 4 g + e % 4, output channel 32 rt + rb (lanes r < ROWS).
+        // acc[e] of lane (r, g): token 32 (m0 + m) + 8 (e / 4) + 4 g + e % 4, output channel 32 rt + rb (lanes r < ROWS).
         // 1024 outputs, 512 threads: thread t sums register e = t / 64 and e + 8 of lane t % 64 over the waves.
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -131,7 +136,7 @@ __global__ __launch_bounds__(kDecWaves * 64) void gemm_decode_kernel(TiledGemmPa
             float sum = 0.f;
 #pragma unroll
             for (int w = 0; w < kDecWaves; ++w) sum += part[w][e][lane];
-            const int tok = 32 * m + 8 * (e / 4) + 4 * g + (e % 4);
+            const int tok = 32 * (m0 + m) + 8 * (e / 4) + 4 * g + (e % 4);
             const int col = rt * 32 + rb;
             if (r < ROWS && tok < p.T && col < p.N) {
                 if (OUT_BF16) ((uint16_t*)p.y)[(int64_t)tok * p.ldy + col] = dec_f32_to_bf16_rne(sum);
@@ -142,8 +147,8 @@ __global__ __launch_bounds__(kDecWaves * 64) void gemm_decode_kernel(TiledGemmPa
 }
 
 template <int ROWS, int MT>
-static void launch_decode_rows(const TiledGemmParams& p, unsigned tiles, hipStream_t stream) {
-    dim3 grid(tiles * (32 / ROWS)), block(kDecWaves * 64);
+static void launch_decode_rows(const TiledGemmParams& p, unsigned tiles, unsigned passes, hipStream_t stream) {
+    dim3 grid(tiles * (32 / ROWS), passes), block(kDecWaves * 64);
     if (p.out_bf16) hipLaunchKernelGGL((gemm_decode_kernel<true, ROWS, MT>), grid, block, 0, stream, p);
     else hipLaunchKernelGGL((gemm_decode_kernel<false, ROWS, MT>), grid, block, 0, stream, p);
 }
@@ -154,12 +159,14 @@ hipError_t launch_gemm_decode(const TiledGemmParams& p, hipStream_t stream) {
     // Measured at N = 4096, K = 14336: halving the row tiles (256 workgroups instead of 128) gains 13 %;
     // quartering them, 16 waves per workgroup or deeper register rings all lose.
     const bool cut = tiles < (unsigned)kNumCU;
+    // 65..128 tokens: two passes of two row tiles each (blockIdx.y), the weights of the second mostly from cache
+    const unsigned passes = p.T <= 64 ? 1u : 2u;
     if (p.T <= 32) {
-        if (cut) launch_decode_rows<16, 1>(p, tiles, stream);
-        else launch_decode_rows<32, 1>(p, tiles, stream);
+        if (cut) launch_decode_rows<16, 1>(p, tiles, passes, stream);
+        else launch_decode_rows<32, 1>(p, tiles, passes, stream);
     } else {
-        if (cut) launch_decode_rows<16, 2>(p, tiles, stream);
-        else launch_decode_rows<32, 2>(p, tiles, stream);
+        if (cut) launch_decode_rows<16, 2>(p, tiles, passes, stream);
+        else launch_decode_rows<32, 2>(p, tiles, passes, stream);
     }
     return hipGetLastError();
 }

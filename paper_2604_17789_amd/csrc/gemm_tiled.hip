@@ -455,7 +455,17 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
 }
 
 hipError_t launch_gemm_tiled(const TiledGemmParams& p, hipStream_t stream) {
-    if (p.T <= kDecodeMaxT) return launch_gemm_decode(p, stream);    // weight-streaming shape
+    // Weight-streaming shapes go to the decode kernel: always up to 64 tokens; from 65 to 128 (two passes
+    // over the weights) when that beats this kernel, which then has at most N / 256 of the 256 CUs busy for
+    // GP / 8 steps of about a microsecond.  Times in microseconds, fitted to measurements at the LLaMA-3-8B shapes.
+    if (p.T <= 64) return launch_gemm_decode(p, stream);
+    if (p.T <= kDecodeMaxT) {
+        const double weight_bytes = (double)p.N * p.GP * 17.0;
+        const double t_decode = 2.0 * (2.5 + weight_bytes / 2.8e6);
+        const int tiles = (p.N + kBN - 1) / kBN;
+        const double t_prefill = 3.0 + 1.05 * (p.GP / 8) * ((tiles + kNumCU - 1) / kNumCU);
+        if (t_decode < t_prefill) return launch_gemm_decode(p, stream);
+    }
     static std::atomic<int> configured{0};
     if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)gemm_tiled_kernel<true>,

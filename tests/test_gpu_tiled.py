@@ -140,6 +140,9 @@ GEMM_SHAPES = [
     (33, 200, 1184),      # decode kernel with two activation row tiles, the second almost empty
     (64, 4100, 288),      # two full activation row tiles, 129 weight row tiles (each cut in two)
     (50, 8200, 544),      # two activation row tiles, 257 weight row tiles (whole tiles per workgroup)
+    (96, 300, 1184),      # decode kernel in two passes; the second pass has one real row tile
+    (128, 4100, 288),     # decode kernel in two passes of two full row tiles
+    (100, 8200, 544),     # two passes, whole weight row tiles per workgroup, ragged last token tile
     (130, 70, 32),        # a single group (one K step of mostly padding)
     (200, 264, 2304),
     (129, 513, 1312),
