@@ -263,3 +263,43 @@ def test_decode_configs(env, name):
     assert np.mean(mxfp4.unpack_codes(ac) != mxfp4.unpack_codes(c_ref)) < 1e-3
     ref = linear.mxfp4_gemm(ac, asc, bc, bsc)
     assert rel_fro(y.cpu().numpy(), ref) <= GEMM_TOL
+
+
+def test_graph_replay_matches_eager_launches(env):
+    """The bench times a captured graph of the two kernels: every replay must give what eager launches give,
+    also after the inputs behind the captured pointers have changed (prefill and decode kernels)."""
+    torch, duqpp = env
+    for (T, N, K) in [(300, 520, 1184), (16, 300, 2048)]:
+        R = to_dev(wl.make_rotation_blocks("graph", K // 32), torch)
+        w = to_dev_bf16(wl.make_weights("graph", N, K, 0.02), torch)
+        bct, bst = duqpp.quantize_weights_tiled(w, R)
+        x = to_dev_bf16(wl.make_activations("graph-0", T, K, (wl.OutlierSpec(4, 50.0),)), torch)
+        cb, sb = duqpp.tiled_bytes(T, K)
+        act = torch.empty(cb, dtype=torch.uint8, device=x.device)
+        ast = torch.empty(sb, dtype=torch.uint8, device=x.device)
+        y = torch.empty((T, N), dtype=torch.float32, device=x.device)
+
+        def run():
+            duqpp.rotate_quantize_tiled(x, R, out=(act, ast))
+            duqpp.mxfp4_gemm_tiled(act, ast, bct, bst, T, N, K, out=y)
+
+        run()                                              # first call outside the capture (function attributes)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                run()
+        torch.cuda.synchronize()
+        for rep in range(3):
+            x.copy_(to_dev_bf16(wl.make_activations(f"graph-{rep + 1}", T, K, (wl.OutlierSpec(4, 50.0),)), torch))
+            y.zero_()
+            g.replay()
+            torch.cuda.synchronize()
+            y_graph, a_graph = y.clone(), act.clone()
+            y.zero_()
+            run()
+            torch.cuda.synchronize()
+            assert torch.equal(a_graph, act) and torch.equal(y_graph, y), (T, N, K, rep)
+            assert float(y.abs().max()) > 0
