@@ -90,6 +90,7 @@ struct TiledGemmParams {
     void* y; int64_t ldy; int out_bf16;
 };
 hipError_t launch_gemm_tiled(const TiledGemmParams& p, hipStream_t stream);     // picks the kernel by shape
+hipError_t launch_gemm_tiled_small(const TiledGemmParams& p, hipStream_t stream);   // 64 x 128 tiles
 constexpr int kDecodeMaxT = 128;   // up to four activation row tiles go to the weight-streaming kernel
 hipError_t launch_gemm_decode(const TiledGemmParams& p, hipStream_t stream);    // T <= kDecodeMaxT
 

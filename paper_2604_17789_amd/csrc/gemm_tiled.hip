@@ -29,18 +29,12 @@
 #include <type_traits>
 
 #include "duqpp_internal.h"
+#include "gemm_tiled_common.h"
 
 namespace duqpp {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef int i32x8 __attribute__((ext_vector_type(8)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
-typedef const __attribute__((address_space(1))) void* global_void_ptr;
-
 constexpr int kBM = 128, kBN = 256;
 constexpr int kMT = kBM / 32, kNT = kBN / 32;           // row tiles of A / B per workgroup
-constexpr int kTileStepBytes = 8 * 512;                 // one row tile, one K step (8 groups)
 constexpr int kStageBytes = (kMT + kNT) * kTileStepBytes + 4 * 1024;   // codes + scale words
 constexpr int kStages = 3;
 constexpr int kGemmLdsBytes = kStages * kStageBytes;    // 159744 of the CU's 163840
@@ -56,66 +50,6 @@ struct Frags {
 struct Scales {
     uint32_t a[2], b[4];
 };
-
-// M0 carries the LDS destination of an LDS-DMA transfer; the compiler reserves the register but
-// has no use for it in this kernel, and the clobber tells it the value does not survive.
-#pragma clang diagnostic ignored "-Winline-asm"
-
-// Four KiB-sized LDS-DMA transfers: global [src, src + 4096) (64 lanes x 16 B per transfer) to LDS
-// [lds_dst, lds_dst + 4096).  The immediate offset advances both addresses.
-__device__ __forceinline__ void dma_4k(const uint8_t* src_lane, uint32_t lds_dst) {
-    asm volatile(
-        "s_mov_b32 m0, %1\n\t"
-        "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %0, off\n\t"
-        "global_load_lds_dwordx4 %0, off offset:1024\n\t"
-        "global_load_lds_dwordx4 %0, off offset:2048\n\t"
-        "global_load_lds_dwordx4 %0, off offset:3072"
-        :
-        : "v"(src_lane), "s"(lds_dst)
-        : "memory", "m0");
-}
-
-// One KiB-sized transfer with a compile-time offset applied to both addresses.
-template <int OFF>
-__device__ __forceinline__ void dma_1k_at(const uint8_t* src_lane, uint32_t lds_dst) {
-    asm volatile(
-        "s_mov_b32 m0, %1\n\t"
-        "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %0, off offset:%2"
-        :
-        : "v"(src_lane), "s"(lds_dst), "n"(OFF)
-        : "memory", "m0");
-}
-
-__device__ __forceinline__ void dma_1k(const uint8_t* src_lane, uint32_t lds_dst) {
-    asm volatile(
-        "s_mov_b32 m0, %1\n\t"
-        "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %0, off"
-        :
-        : "v"(src_lane), "s"(lds_dst)
-        : "memory", "m0");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
-// Every LDS access this wave has issued has completed, then workgroup barrier: what a wave writes to LDS
-// after the barrier cannot overtake a read another wave issued before it.
-__device__ __forceinline__ void workgroup_barrier() {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
-__device__ __forceinline__ i32x8 fp4_operand(const u32x4& v) {
-    i32x8 r = {(int)v[0], (int)v[1], (int)v[2], (int)v[3], 0, 0, 0, 0};
-    return r;
-}
-
-#define DUQPP_MFMA(ACC, A, B, SA, SB, SEL) \
-    ACC = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fp4_operand(A), fp4_operand(B), ACC, 4, 4, SEL, (int)(SA), SEL, (int)(SB))
 
 // the eight MFMAs of one quarter step: groups 4 g + SEL of every row tile pair
 #define DUQPP_MFMA8(F, S, SEL)                                    \
@@ -137,12 +71,6 @@ __device__ __forceinline__ void read_frags(Frags& f, const uint8_t* pa, const ui
     f.b[1] = *(const u32x4*)(pb + 4096 + Q * 512);
     f.b[2] = *(const u32x4*)(pb + 8192 + Q * 512);
     f.b[3] = *(const u32x4*)(pb + 12288 + Q * 512);
-}
-
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
 }
 
 template <bool OUT_BF16>
@@ -466,6 +394,8 @@ hipError_t launch_gemm_tiled(const TiledGemmParams& p, hipStream_t stream) {
         const double t_prefill = 3.0 + 1.05 * (p.GP / 8) * ((tiles + kNumCU - 1) / kNumCU);
         if (t_decode < t_prefill) return launch_gemm_decode(p, stream);
     }
+    // Too few 128 x 256 tiles to occupy the chip: 64 x 128 tiles, four times as many, two workgroups per CU.
+    if (((p.T + kBM - 1) / kBM) * ((p.N + kBN - 1) / kBN) < kNumCU / 2) return launch_gemm_tiled_small(p, stream);
     static std::atomic<int> configured{0};
     if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)gemm_tiled_kernel<true>,
