@@ -56,7 +56,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards by tokens or output channels "
-              "without exchange, see DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "without any exchange between GPUs); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

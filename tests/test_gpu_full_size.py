@@ -74,3 +74,61 @@ def test_headline_config_full_size():
     assert rel_fro(y32_th[:, cols], ref_cols) <= 1e-5
     np.testing.assert_array_equal(bf16_dev_to_bits(y16_t), linear.round_to_bf16_bits(y32_th))
     assert torch.equal(y16_t, yf_t)
+
+
+def _tiled_path_sampled(name, T, K, N, outliers, w_std, out_dtype, n_rows=48, n_cols=48):
+    """The tiled path exactly as the bench launches it, at full size: rotate+quantise checked through the
+    quantiser on sampled rows (rotation against fp64, codes bit-exact on the device's own rotated values via
+    the row-major call, which must agree with the tiled call), the product on sampled rows and columns."""
+    import torch
+
+    import paper_2604_17789_amd as duqpp
+    print(f"[full] {name}: generating T={T} K={K} N={N}", flush=True)
+    xb = wl.make_activations(name, T, K, outliers)
+    wb = wl.make_weights(name, N, K, w_std)
+    R = wl.make_rotation_blocks(name, K // 32)
+    x, w, Rd = to_dev_bf16(xb, torch), to_dev_bf16(wb, torch), to_dev(R, torch)
+    del wb
+    print(f"[full] {name}: device", flush=True)
+    bct, bst = duqpp.quantize_weights_tiled(w, Rd)
+    act, ast = duqpp.rotate_quantize_tiled(x, Rd)
+    y = duqpp.mxfp4_gemm_tiled(act, ast, bct, bst, T, N, K, out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(T + N)
+    rows = np.sort(rng.choice(T, n_rows, replace=False))
+    cols = np.sort(rng.choice(N, n_cols, replace=False))
+
+    # rotate+quantise on the sampled token rows: the row-major call on just those rows gives the same codes
+    # as the tiled call on all rows (rows are independent), plus the rotated values the quantiser saw
+    xs = x[torch.from_numpy(rows).to(x.device)].contiguous()
+    c_rm, s_rm, yrot = duqpp.rotate_quantize(xs, Rd, return_rotated=True)
+    torch.cuda.synchronize()
+    a_c, a_s, pc, ps = untile_np(act.cpu().numpy(), ast.cpu().numpy(), T, K)
+    assert np.all(pc == 0) and np.all(ps == 127)
+    np.testing.assert_array_equal(a_c[rows], c_rm.cpu().numpy())
+    np.testing.assert_array_equal(a_s[rows], s_rm.cpu().numpy())
+    xf = wl.bf16_bits_to_f32(xb[rows])
+    assert rotation_error_ratio(yrot.cpu().numpy(), rotation.rotate(xf, R), xf) <= 1e-5
+    c_ref, s_ref = mxfp4.quantize(yrot.cpu().numpy())
+    np.testing.assert_array_equal(c_rm.cpu().numpy(), c_ref)
+    np.testing.assert_array_equal(s_rm.cpu().numpy(), s_ref)
+
+    print(f"[full] {name}: oracle on sampled rows and columns", flush=True)
+    b_c, b_s, _, _ = untile_np(bct.cpu().numpy(), bst.cpu().numpy(), N, K)
+    yh = y.float().cpu().numpy()
+    tol = 1e-5 if out_dtype == 0 else 2.0 ** -8      # bf16 output: one rounding of the fp32 result
+    assert rel_fro(yh[rows], linear.mxfp4_gemm(a_c[rows], a_s[rows], b_c, b_s)) <= tol
+    assert rel_fro(yh[:, cols], linear.mxfp4_gemm(a_c, a_s, b_c[cols], b_s[cols])) <= tol
+
+
+def test_70b_down_proj_full_size():
+    """LLaMA-3-70B down_proj prefill (T=4096, K=28672, N=8192, fp32 out): four tiles per persistent workgroup,
+    112 K steps each."""
+    cfg = wl.CONFIGS["c4_70b_down_prefill"]
+    _tiled_path_sampled("c4", cfg["T"], cfg["K"], cfg["N"], cfg["outliers"], cfg["w_std"], 0, n_rows=32, n_cols=32)
+
+
+def test_layer_set_gate_proj_full_size():
+    """gate_proj of the 8B layer set at T=8192 (K=4096, N=14336, bf16 out): fourteen tiles per persistent
+    workgroup, the transfer pipeline crossing every tile boundary."""
+    _tiled_path_sampled("c5-gate", 8192, 4096, 14336, (), 0.02, 1)
