@@ -43,6 +43,8 @@ def main():
     ap.add_argument("--config", default="c2_8b_down_prefill")
     ap.add_argument("--sets", type=int, default=8, help="distinct buffer sets the batches rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-machine-probe", action="store_true",
+                    help="skip the two measurements of what the machine sustains (FP4 MFMA loop, device copy)")
     ap.add_argument("--eager", action="store_true", help="time eager launches only (no HIP graph capture)")
     ap.add_argument("--smoothing", action="store_true",
                     help="run the smoothed form of the path (Eq. 5 as written): a synthetic smoothing diagonal is "
@@ -267,6 +269,38 @@ def main():
                               "achieved": round(weight_bytes / (gemm_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS,
                               "unit": "GB/s", "frac": round(weight_bytes / (gemm_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
                               "traffic": None}
+
+    # ---- what the machine sustains, measured here, beside the published peaks ---------------
+    # FP4 MFMA: the library's register-resident loop on bit patterns of the quantised weights (the clock the chip
+    # settles to depends on the operands); HBM: a plain 1 GiB device copy (reads + writes over time).
+    if not args.no_machine_probe:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        pc = sets[0][-1]["bc"]
+        duqpp.probe_fp4_mfma(pc, 2000)
+        torch.cuda.synchronize()
+        e0.record()
+        _, probe_flops = duqpp.probe_fp4_mfma(pc, 6000)
+        e1.record()
+        torch.cuda.synchronize()
+        sustained = probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(4):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbps = 4 * 2.0 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del src, dst
+        result["machine"] = {"fp4_mfma_sustained_TFLOP/s": round(sustained, 1),
+                             "fp4_mfma_sustained_frac_of_peak": round(sustained / FP4_PEAK_TFLOPS, 4),
+                             "hbm_copy_GB/s": round(copy_gbps, 1),
+                             "hbm_copy_frac_of_peak": round(copy_gbps / HBM_PEAK_GBPS, 4)}
+        if T > 32:
+            result["roofline"]["frac_of_sustained"] = round(gemm_tflops / sustained, 4)
+        result["roofline_rotate_quantize"]["frac_of_copy_rate"] = round(rotq_gbps / copy_gbps, 4)
 
     # ---- the CPU oracle on a bounded sample of the same workload ---------------------------
     if not args.no_cpu_baseline:

@@ -47,6 +47,8 @@ def _load():
     L.duqpp_mxfp4_gemm_tiled.argtypes = [u8p, u8p, u8p, u8p, i64, i64, i64, vp, ci, i64, vp]
     L.duqpp_rotq_gemm_tiled.argtypes = [vp, i64, fp, i64, u8p, u8p, i64, i64, i64, vp, ci, i64, vp, sz, vp]
     L.duqpp_fold_smoothing.argtypes = [fp, i64, fp, i64, fp, fp, vp]
+    L.duqpp_probe_fp4_mfma.argtypes = [u8p, sz, i64, fp, ctypes.POINTER(ctypes.c_double), vp]
+    L.duqpp_probe_fp4_mfma.restype = ci
     for name in ("duqpp_tiled_bytes", "duqpp_tile_operand", "duqpp_untile_operand", "duqpp_quantize_weights_tiled",
                  "duqpp_rotate_quantize_tiled", "duqpp_mxfp4_gemm_tiled", "duqpp_rotq_gemm_tiled",
                  "duqpp_fold_smoothing"):
@@ -316,3 +318,14 @@ def fold_smoothing(R, lam):
     _check(lib.duqpp_fold_smoothing(R.data_ptr(), _n_rblocks(R), lam.data_ptr(), K, R_act.data_ptr(),
                                     R_wgt.data_ptr(), _stream()), "duqpp_fold_smoothing")
     return R_act, R_wgt
+
+
+def probe_fp4_mfma(codes, iters, out=None):
+    """Measurement only: enqueue the register-resident FP4 MFMA loop; returns (out, flops of the launch)."""
+    _dev(codes, torch.uint8, "codes")
+    if out is None:
+        out = torch.empty(256 * 256, dtype=torch.float32, device=codes.device)
+    flops = ctypes.c_double(0.0)
+    _check(lib.duqpp_probe_fp4_mfma(codes.data_ptr(), codes.numel(), iters, out.data_ptr(), ctypes.byref(flops),
+                                    _stream()), "duqpp_probe_fp4_mfma")
+    return out, flops.value

@@ -83,6 +83,14 @@ struct FoldParams {
 };
 hipError_t launch_fold_smoothing(const FoldParams& p, hipStream_t stream);
 
+// ---- measurement aid (probe.hip) --------------------------------------------------------------
+struct ProbeParams {
+    const uint8_t* codes; int pieces;   // pieces of 2 KiB of code bytes used as operand patterns
+    int64_t iters;                      // each wave issues 8 * iters MFMAs
+    float* out;                         // [kNumCU * 256]
+};
+hipError_t launch_probe_fp4_mfma(const ProbeParams& p, hipStream_t stream);
+
 struct TiledGemmParams {
     const uint8_t* a_codes; const uint8_t* a_scales;   // tiled, T rows
     const uint8_t* b_codes; const uint8_t* b_scales;   // tiled, N rows
