@@ -164,6 +164,28 @@ int duqpp_mxfp4_gemm_tiled(const uint8_t* a_codes_t, const uint8_t* a_scales_t,
                            void* y, int out_dtype, int64_t ldy, void* stream);
 
 /*
+ * TEST AND MEASUREMENT ONLY: duqpp_mxfp4_gemm_tiled on one named kernel instead of the one the library would
+ * pick for the shape, so that every kernel can be checked at every shape.  Same arguments, checks and result.
+ * A kernel that cannot run the call returns DUQPP_ERR_SHAPE: the decode kernel takes T <= 128; the 256 x 256
+ * kernel with bf16 output needs y 16-byte aligned and N, ldy multiples of 8.
+ * duqpp_gemm_kernel_for reports (host, pure) which kernel DUQPP_GEMM_KERNEL_AUTO resolves to; it assumes an
+ * aligned output.
+ */
+enum {
+    DUQPP_GEMM_KERNEL_AUTO = 0,
+    DUQPP_GEMM_KERNEL_DECODE = 1,   /* weight streaming, T <= 128 */
+    DUQPP_GEMM_KERNEL_SMALL = 2,    /* 64 x 128 tiles */
+    DUQPP_GEMM_KERNEL_MID = 3,      /* 128 x 256 tiles */
+    DUQPP_GEMM_KERNEL_LARGE = 4     /* 256 x 256 tiles */
+};
+int duqpp_mxfp4_gemm_tiled_on(int kernel,
+                              const uint8_t* a_codes_t, const uint8_t* a_scales_t,
+                              const uint8_t* b_codes_t, const uint8_t* b_scales_t,
+                              int64_t T, int64_t N, int64_t K,
+                              void* y, int out_dtype, int64_t ldy, void* stream);
+int duqpp_gemm_kernel_for(int64_t T, int64_t N, int64_t K, int out_dtype);
+
+/*
  * duqpp_rotq_gemm with tiled weights.  workspace: at least the two sizes duqpp_tiled_bytes(T, K)
  * reports, each rounded up to 256, 256-byte aligned.
  */

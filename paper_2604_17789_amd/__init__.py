@@ -7,6 +7,12 @@ There is no CPU or PyTorch fallback: importing without the built library raises.
 from .binding import (  # noqa: F401
     BF16,
     F32,
+    KERNEL_AUTO,
+    KERNEL_DECODE,
+    KERNEL_LARGE,
+    KERNEL_MID,
+    KERNEL_SMALL,
+    gemm_kernel_for,
     DuqppError,
     fold_smoothing,
     gemm_workspace_bytes,

@@ -8,6 +8,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libduqpp.so"
 
 F32, BF16 = 0, 1
+# kernels of the tiled GEMM (the DUQPP_GEMM_KERNEL_* values of the header)
+KERNEL_AUTO, KERNEL_DECODE, KERNEL_SMALL, KERNEL_MID, KERNEL_LARGE = 0, 1, 2, 3, 4
 
 
 class DuqppError(RuntimeError):
@@ -45,6 +47,10 @@ def _load():
     L.duqpp_quantize_weights_tiled.argtypes = [vp, i64, i64, i64, fp, i64, u8p, u8p, vp]
     L.duqpp_rotate_quantize_tiled.argtypes = [vp, i64, i64, i64, fp, i64, u8p, u8p, vp]
     L.duqpp_mxfp4_gemm_tiled.argtypes = [u8p, u8p, u8p, u8p, i64, i64, i64, vp, ci, i64, vp]
+    L.duqpp_mxfp4_gemm_tiled_on.argtypes = [ci, u8p, u8p, u8p, u8p, i64, i64, i64, vp, ci, i64, vp]
+    L.duqpp_mxfp4_gemm_tiled_on.restype = ci
+    L.duqpp_gemm_kernel_for.argtypes = [i64, i64, i64, ci]
+    L.duqpp_gemm_kernel_for.restype = ci
     L.duqpp_rotq_gemm_tiled.argtypes = [vp, i64, fp, i64, u8p, u8p, i64, i64, i64, vp, ci, i64, vp, sz, vp]
     L.duqpp_fold_smoothing.argtypes = [fp, i64, fp, i64, fp, fp, vp]
     L.duqpp_probe_fp4_mfma.argtypes = [u8p, sz, i64, fp, ctypes.POINTER(ctypes.c_double), vp]
@@ -273,12 +279,24 @@ def quantize_weights_tiled(w, R, out=None):
     return _rows_op_tiled(lib.duqpp_quantize_weights_tiled, "duqpp_quantize_weights_tiled", w, R, out)
 
 
-def mxfp4_gemm_tiled(a_codes_t, a_scales_t, b_codes_t, b_scales_t, T, N, K, out_dtype=F32, out=None):
+def gemm_kernel_for(T, N, K, out_dtype=F32):
+    k = lib.duqpp_gemm_kernel_for(T, N, K, out_dtype)
+    if k < 0:
+        _check(k, "duqpp_gemm_kernel_for")
+    return k
+
+
+def mxfp4_gemm_tiled(a_codes_t, a_scales_t, b_codes_t, b_scales_t, T, N, K, out_dtype=F32, out=None, kernel=KERNEL_AUTO):
     for t, n in ((a_codes_t, "a_codes_t"), (a_scales_t, "a_scales_t"), (b_codes_t, "b_codes_t"), (b_scales_t, "b_scales_t")):
         _dev(t, torch.uint8, n)
     if (a_codes_t.numel(), a_scales_t.numel()) != tiled_bytes(T, K) or (b_codes_t.numel(), b_scales_t.numel()) != tiled_bytes(N, K):
         raise ValueError("operand sizes disagree with T, N, K")
     y = _out(T, N, out_dtype, a_codes_t.device, out)
+    if kernel != KERNEL_AUTO:
+        _check(lib.duqpp_mxfp4_gemm_tiled_on(kernel, a_codes_t.data_ptr(), a_scales_t.data_ptr(), b_codes_t.data_ptr(),
+                                             b_scales_t.data_ptr(), T, N, K, y.data_ptr(), out_dtype, y.stride(0), _stream()),
+               "duqpp_mxfp4_gemm_tiled_on")
+        return y
     _check(lib.duqpp_mxfp4_gemm_tiled(a_codes_t.data_ptr(), a_scales_t.data_ptr(), b_codes_t.data_ptr(), b_scales_t.data_ptr(),
                                       T, N, K, y.data_ptr(), out_dtype, y.stride(0), _stream()), "duqpp_mxfp4_gemm_tiled")
     return y

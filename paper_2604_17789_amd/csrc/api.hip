@@ -253,6 +253,34 @@ int duqpp_mxfp4_gemm_tiled(const uint8_t* a_codes_t, const uint8_t* a_scales_t, 
     return launch_gemm_tiled(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
 }
 
+int duqpp_mxfp4_gemm_tiled_on(int kernel, const uint8_t* a_codes_t, const uint8_t* a_scales_t,
+                              const uint8_t* b_codes_t, const uint8_t* b_scales_t, int64_t T, int64_t N, int64_t K,
+                              void* y, int out_dtype, int64_t ldy, void* stream) {
+    if (kernel < DUQPP_GEMM_KERNEL_AUTO || kernel > DUQPP_GEMM_KERNEL_LARGE) return DUQPP_ERR_SHAPE;
+    int st = duqpp_validate_mxfp4_gemm(a_codes_t, a_scales_t, b_codes_t, b_scales_t, T, N, K, y, out_dtype, ldy,
+                                       nullptr, 0, 2);
+    if (st != DUQPP_OK) return st;
+    if (!aligned_to(a_codes_t, 256) || !aligned_to(a_scales_t, 256) || !aligned_to(b_codes_t, 256) ||
+        !aligned_to(b_scales_t, 256))
+        return DUQPP_ERR_ALIGN;
+    TiledGemmParams p{a_codes_t, a_scales_t, b_codes_t, b_scales_t, (int)T, (int)N, (int)tiled_groups(K / 32),
+                      y, ldy, out_dtype == DUQPP_BF16};
+    if (kernel == DUQPP_GEMM_KERNEL_DECODE && T > kDecodeMaxT) return DUQPP_ERR_SHAPE;
+    if (kernel == DUQPP_GEMM_KERNEL_LARGE && !gemm_tiled_large_accepts(p)) return DUQPP_ERR_SHAPE;
+    st = check_device();
+    if (st != DUQPP_OK) return st;
+    return launch_gemm_tiled_as(p, kernel, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
+}
+
+int duqpp_gemm_kernel_for(int64_t T, int64_t N, int64_t K, int out_dtype) {
+    if (T < 1 || N < 1 || K < 32 || (K % 32) != 0 || T > (int64_t)1 << 30 || N > (int64_t)1 << 30 || K > (int64_t)1 << 30)
+        return DUQPP_ERR_SHAPE;
+    if (out_dtype != DUQPP_F32 && out_dtype != DUQPP_BF16) return DUQPP_ERR_DTYPE;
+    TiledGemmParams p{nullptr, nullptr, nullptr, nullptr, (int)T, (int)N, (int)tiled_groups(K / 32),
+                      nullptr, N, out_dtype == DUQPP_BF16};
+    return choose_gemm_kernel(p);
+}
+
 int duqpp_rotq_gemm_tiled(const void* x_bf16, int64_t ldx, const float* R, int64_t n_rblocks,
                           const uint8_t* b_codes_t, const uint8_t* b_scales_t, int64_t T, int64_t N, int64_t K,
                           void* y, int out_dtype, int64_t ldy, void* workspace, size_t workspace_bytes,

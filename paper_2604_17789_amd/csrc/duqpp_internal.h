@@ -98,7 +98,11 @@ struct TiledGemmParams {
     void* y; int64_t ldy; int out_bf16;
 };
 hipError_t launch_gemm_tiled(const TiledGemmParams& p, hipStream_t stream);     // picks the kernel by shape
+int choose_gemm_kernel(const TiledGemmParams& p);                              // the DUQPP_GEMM_KERNEL_* it picks
+hipError_t launch_gemm_tiled_as(const TiledGemmParams& p, int kernel, hipStream_t stream);   // a named kernel
 hipError_t launch_gemm_tiled_small(const TiledGemmParams& p, hipStream_t stream);   // 64 x 128 tiles
+hipError_t launch_gemm_tiled_large(const TiledGemmParams& p, hipStream_t stream);   // 256 x 256 tiles
+bool gemm_tiled_large_accepts(const TiledGemmParams& p);                           // output alignment the large kernel needs
 constexpr int kDecodeMaxT = 128;   // up to four activation row tiles go to the weight-streaming kernel
 hipError_t launch_gemm_decode(const TiledGemmParams& p, hipStream_t stream);    // T <= kDecodeMaxT
 

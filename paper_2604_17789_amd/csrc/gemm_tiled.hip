@@ -382,20 +382,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
     }                                                      // ---- tile loop
 }
 
-hipError_t launch_gemm_tiled(const TiledGemmParams& p, hipStream_t stream) {
-    // Weight-streaming shapes go to the decode kernel: always up to 64 tokens; from 65 to 128 (two passes
-    // over the weights) when that beats this kernel, which then has at most N / 256 of the 256 CUs busy for
-    // GP / 8 steps of about a microsecond.  Times in microseconds, fitted to measurements at the LLaMA-3-8B shapes.
-    if (p.T <= 64) return launch_gemm_decode(p, stream);
-    if (p.T <= kDecodeMaxT) {
-        const double weight_bytes = (double)p.N * p.GP * 17.0;
-        const double t_decode = 2.0 * (2.5 + weight_bytes / 2.8e6);
-        const int tiles = (p.N + kBN - 1) / kBN;
-        const double t_prefill = 3.0 + 1.05 * (p.GP / 8) * ((tiles + kNumCU - 1) / kNumCU);
-        if (t_decode < t_prefill) return launch_gemm_decode(p, stream);
-    }
-    // Too few 128 x 256 tiles to occupy the chip: 64 x 128 tiles, four times as many, two workgroups per CU.
-    if (((p.T + kBM - 1) / kBM) * ((p.N + kBN - 1) / kBN) < kNumCU / 2) return launch_gemm_tiled_small(p, stream);
+// 128 x 256 tiles, persistent workgroups, any shape.
+hipError_t launch_gemm_tiled_mid(const TiledGemmParams& p, hipStream_t stream) {
     static std::atomic<int> configured{0};
     if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)gemm_tiled_kernel<true>,
@@ -414,6 +402,49 @@ hipError_t launch_gemm_tiled(const TiledGemmParams& p, hipStream_t stream) {
     if (p.out_bf16) hipLaunchKernelGGL(gemm_tiled_kernel<true>, grid, block, kGemmLdsBytes, stream, p);
     else hipLaunchKernelGGL(gemm_tiled_kernel<false>, grid, block, kGemmLdsBytes, stream, p);
     return hipGetLastError();
+}
+
+// Which kernel runs a shape.
+int choose_gemm_kernel(const TiledGemmParams& p) {
+    // Weight-streaming shapes go to the decode kernel: always up to 64 tokens; from 65 to 128 (two passes
+    // over the weights) when that beats the 128 x 256 kernel, which then has at most N / 256 of the 256 CUs busy
+    // for GP / 8 steps of about a microsecond.  Times in microseconds, fitted to measurements at the LLaMA-3-8B shapes.
+    if (p.T <= 64) return DUQPP_GEMM_KERNEL_DECODE;
+    const int64_t mid_tiles = (int64_t)((p.T + kBM - 1) / kBM) * ((p.N + kBN - 1) / kBN);
+    if (p.T <= kDecodeMaxT) {
+        const double weight_bytes = (double)p.N * p.GP * 17.0;
+        const double t_decode = 2.0 * (2.5 + weight_bytes / 2.8e6);
+        const int tiles = (p.N + kBN - 1) / kBN;
+        const double t_prefill = 3.0 + 1.05 * (p.GP / 8) * ((tiles + kNumCU - 1) / kNumCU);
+        if (t_decode < t_prefill) return DUQPP_GEMM_KERNEL_DECODE;
+    }
+    // Too few 128 x 256 tiles to occupy the chip: 64 x 128 tiles, four times as many, two workgroups per CU.
+    if (mid_tiles < kNumCU / 2) return DUQPP_GEMM_KERNEL_SMALL;
+    // 256 x 256 tiles do a flop in about 0.8 of the time of 128 x 256 tiles (less L2 and LDS traffic per flop),
+    // i.e. a tile with twice the work costs 1.6 of a 128 x 256 tile: they win when the rounds over the 256 CUs come out
+    // cheaper, which needs at least 256 of them or so.
+    if (gemm_tiled_large_accepts(p)) {
+        const int64_t large_tiles = (int64_t)((p.T + 255) / 256) * ((p.N + 255) / 256);
+        const double t_mid = (double)((mid_tiles + kNumCU - 1) / kNumCU);
+        const double t_large = 1.6 * (double)((large_tiles + kNumCU - 1) / kNumCU);
+        if (t_large < t_mid) return DUQPP_GEMM_KERNEL_LARGE;
+    }
+    return DUQPP_GEMM_KERNEL_MID;
+}
+
+hipError_t launch_gemm_tiled_as(const TiledGemmParams& p, int kernel, hipStream_t stream) {
+    switch (kernel) {
+        case DUQPP_GEMM_KERNEL_AUTO: return launch_gemm_tiled_as(p, choose_gemm_kernel(p), stream);
+        case DUQPP_GEMM_KERNEL_DECODE: return p.T <= kDecodeMaxT ? launch_gemm_decode(p, stream) : hipErrorInvalidValue;
+        case DUQPP_GEMM_KERNEL_SMALL: return launch_gemm_tiled_small(p, stream);
+        case DUQPP_GEMM_KERNEL_MID: return launch_gemm_tiled_mid(p, stream);
+        case DUQPP_GEMM_KERNEL_LARGE: return launch_gemm_tiled_large(p, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_gemm_tiled(const TiledGemmParams& p, hipStream_t stream) {
+    return launch_gemm_tiled_as(p, DUQPP_GEMM_KERNEL_AUTO, stream);
 }
 
 }  // namespace duqpp

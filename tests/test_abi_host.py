@@ -98,6 +98,30 @@ def test_entry_points_reject_bad_arguments_before_any_launch(lib):
     assert lib.duqpp_fold_smoothing(P, 2, P + 2, 64, P, P, None) == ALIGN
 
 
+def test_kernel_choice_for_the_benchmark_shapes(lib):
+    """Host-side rule that picks the GEMM kernel: weight streaming up to 64 tokens, 64 x 128 tiles when there are too
+    few 128 x 256 tiles for the chip, 256 x 256 tiles when enough of them make up whole rounds over the 256 CUs."""
+    DECODE, SMALL, MID, LARGE = 1, 2, 3, 4
+    F32, BF16 = 0, 1
+    k = lib.duqpp_gemm_kernel_for
+    assert k(64, 4096, 4096, F32) == DECODE                # q_proj reference shape
+    assert k(1, 14336, 4096, F32) == DECODE and k(16, 4096, 14336, F32) == DECODE
+    assert k(512, 4096, 4096, BF16) == SMALL               # 64 tiles of 128 x 256
+    assert k(2048, 4096, 14336, BF16) == MID               # 8B down_proj prefill: 256 tiles of 128 x 256, 128 of 256 x 256
+    assert k(8192, 1024, 4096, BF16) == MID                # k / v projections of the layer set
+    assert k(4096, 8192, 28672, F32) == LARGE              # 70B down_proj prefill: 512 tiles of 256 x 256
+    for N, K in ((4096, 4096), (14336, 4096), (4096, 14336)):
+        assert k(8192, N, K, BF16) == LARGE                # q / o, gate / up, down of the layer set
+    assert k(8192, 4100, 4096, BF16) == MID                # bf16 rows leave in 16-byte pieces: N must be a multiple of 8
+    assert k(8192, 4100, 4096, F32) == LARGE
+    assert k(0, 16, 64, F32) == SHAPE and k(8, 16, 48, F32) == SHAPE and k(8, 16, 64, 7) == DTYPE
+    # forcing a kernel goes through the same host-side checks first
+    assert lib.duqpp_mxfp4_gemm_tiled_on(9, P, P, P, P, 8, 16, 64, P, 0, 16, None) == SHAPE
+    assert lib.duqpp_mxfp4_gemm_tiled_on(DECODE, P, P, P, P, 200, 16, 64, P, 0, 16, None) == SHAPE
+    assert lib.duqpp_mxfp4_gemm_tiled_on(LARGE, P, P, P, P, 200, 20, 64, P, 1, 20, None) == SHAPE
+    assert lib.duqpp_mxfp4_gemm_tiled_on(MID, None, P, P, P, 200, 16, 64, P, 0, 16, None) == NULL
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     import importlib
 
