@@ -423,7 +423,9 @@ int choose_gemm_kernel(const TiledGemmParams& p) {
     // 256 x 256 tiles do a flop in about 0.8 of the time of 128 x 256 tiles (less L2 and LDS traffic per flop),
     // i.e. a tile with twice the work costs 1.6 of a 128 x 256 tile: they win when the rounds over the 256 CUs come out
     // cheaper, which needs at least 256 of them or so.
-    if (gemm_tiled_large_accepts(p)) {
+    // (N a multiple of 8 for either output type, so that the fp32 and the bf16 result of a shape come from the same
+    // kernel and the second is the rounding of the first.)
+    if ((p.N % 8) == 0 && gemm_tiled_large_accepts(p)) {
         const int64_t large_tiles = (int64_t)((p.T + 255) / 256) * ((p.N + 255) / 256);
         const double t_mid = (double)((mid_tiles + kNumCU - 1) / kNumCU);
         const double t_large = 1.6 * (double)((large_tiles + kNumCU - 1) / kNumCU);

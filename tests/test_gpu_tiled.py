@@ -104,6 +104,36 @@ def test_rotate_quantize_tiled_shared_block(env):
     assert np.mean(codes != c_ref) < 1e-4                  # each side rotates in its own precision
 
 
+# Shapes with several token tiles per wave and more workgroups than CUs: short rows (an XCD's workgroups take
+# consecutive column chunks), long rows (an XCD owns column chunks), a ragged last token tile, groups that need padding.
+RQ_LARGE_SHAPES = [(2048, 4096, 0), (4100, 2336, 0), (1000, 14368, 0), (2048, 14336, 0), (2048, 4096, 1), (1000, 14368, 1)]
+
+
+@pytest.mark.parametrize("T,K,shared", RQ_LARGE_SHAPES)
+def test_rotate_quantize_tiled_large(env, T, K, shared):
+    """Codes and scales bit-exact against the oracle's quantiser on the rotated values the row-major call reports
+    (the two calls rotate with the same arithmetic: their codes must be identical), padding as documented, and the
+    rotation itself within tolerance of the oracle."""
+    torch, duqpp = env
+    xb = wl.make_activations(f"gpu-rqtl-{T}-{K}", T, K, (wl.OutlierSpec(min(8, K // 4), 50.0), wl.OutlierSpec(2, 1000.0, 4)))
+    R = wl.make_rotation_blocks(f"gpu-rqtl-{T}-{K}", 1 if shared else K // 32)
+    x, Rd = to_dev_bf16(xb, torch), to_dev(R, torch)
+    print(f"[rotq tiled, large] T={T} K={K} shared={shared}", flush=True)
+    ct, st = duqpp.rotate_quantize_tiled(x, Rd)
+    c_rm, s_rm, yrot = duqpp.rotate_quantize(x, Rd, return_rotated=True)
+    torch.cuda.synchronize()
+    codes, scales, pc, ps = untile_np(ct.cpu().numpy(), st.cpu().numpy(), T, K)
+    assert np.all(pc == 0) and np.all(ps == 127)
+    np.testing.assert_array_equal(codes, c_rm.cpu().numpy())
+    np.testing.assert_array_equal(scales, s_rm.cpu().numpy())
+    yr = yrot.cpu().numpy()
+    c_ref, s_ref = mxfp4.quantize(yr)
+    np.testing.assert_array_equal(codes, c_ref)
+    np.testing.assert_array_equal(scales, s_ref)
+    y_ref = rotation.rotate(wl.bf16_bits_to_f32(xb), R)
+    assert rotation_error_ratio(yr, y_ref, wl.bf16_bits_to_f32(xb)) <= 1e-5
+
+
 def test_quantize_weights_tiled(env):
     torch, duqpp = env
     N, K = 200, 1184
