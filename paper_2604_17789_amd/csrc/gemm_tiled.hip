@@ -323,9 +323,13 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
 #pragma unroll
                     for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
-                        for (int e = 0; e < 16; ++e) {
-                            const int row = 8 * (e / 4) + 4 * g + (e % 4);
-                            *(uint16_t*)(ep + row * kRowPitch + (32 * jj + r) * 2) = f32_to_bf16_rne(acc[i][jj][e]);
+                        for (int e = 0; e < 16; e += 2) {
+                            // rows 8 (e / 4) + 4 g + e % 4 and the next one: the two halves of one packed convert
+                            const bf16x2 b = __builtin_convertvector((f32x2){acc[i][jj][e], acc[i][jj][e + 1]}, bf16x2);
+                            const uint32_t u = __builtin_bit_cast(uint32_t, b);
+                            uint8_t* q = ep + (8 * (e / 4) + 4 * g + (e % 4)) * kRowPitch + (32 * jj + r) * 2;
+                            *(uint16_t*)q = (uint16_t)u;
+                            *(uint16_t*)(q + kRowPitch) = (uint16_t)(u >> 16);
                         }
                     // same wave wrote and reads: program order suffices within a wave
 #pragma unroll

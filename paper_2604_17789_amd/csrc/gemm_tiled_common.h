@@ -10,6 +10,8 @@ namespace duqpp {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));   // fp32 pairs convert to it in one instruction, round to nearest even
 
 constexpr int kTileStepBytes = 8 * 512;                 // codes of one row tile for one K step (8 groups)
 

@@ -41,9 +41,6 @@ constexpr int kLdsBytes = kEpOff + 4 * kEpBytes;         // 157696 of the CU's 1
 constexpr int kDmaOps = 10;                              // transfers per wave per step: 8 x 1 KiB of codes, 2 x 256 B of scales
 constexpr int kGroupM = 8;                               // M tiles per group in the workgroup ordering
 
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-
 struct Frags {
     u32x4 a[4], b[4];
 };
