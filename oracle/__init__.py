@@ -10,10 +10,11 @@ baseline leg call it.
     mxfp4.quantize / dequantize  Eq. 2          (E8M0 scale + E2M1 codes)
     linear.mxfp4_gemm            Eq. 5          (Q(X^) . Q(W^))
     smoothing.*                  Eq. 3          (diagonal Lambda, and its merge into the rotation blocks)
+    construction.*               Sec. 4.2       (greedy construction of the shared rotation block; parity unpinned)
     pipeline.*                   the library's entry points composed from the above
 
 Pinned by tests/test_oracle_*.py (hand-worked groups, exact rational brute force,
 closed forms, invariants).  Not pinned by any number printed in the paper: the
 paper prints no worked numeric example for these equations.
 """
-from . import linear, mxfp4, pipeline, rotation, smoothing  # noqa: F401
+from . import construction, linear, mxfp4, pipeline, rotation, smoothing  # noqa: F401

@@ -15,6 +15,7 @@ from .generators import (  # noqa: F401
     hadamard_blocks,
     identity_blocks,
     make_activations,
+    make_orthogonal_steps,
     make_rotation_blocks,
     make_smoothing_scales,
     make_weights,

@@ -102,6 +102,17 @@ def make_rotation_blocks(name: str, G: int) -> np.ndarray:
     return np.ascontiguousarray(q.astype(np.float32))
 
 
+def make_orthogonal_steps(name: str, steps: int, n: int = BLOCK - 1) -> np.ndarray:
+    """[steps, n, n] fp64 orthogonal matrices (sign-fixed QR of seeded Gaussians): the random draws of the greedy
+    construction of a rotation block, handed to the oracle and to the library alike."""
+    rng = _rng(name, "Qsteps", steps, n)
+    g = rng.standard_normal((steps, n, n))
+    q, r = np.linalg.qr(g)
+    d = np.sign(np.diagonal(r, axis1=1, axis2=2))
+    d[d == 0] = 1.0
+    return np.ascontiguousarray(q * d[:, None, :])
+
+
 def make_smoothing_scales(name: str, K: int, spread: float = 2.0) -> np.ndarray:
     """A synthetic smoothing diagonal [K] fp32: log-uniform in [2^-spread, 2^spread].  Stands in for scales
     calibrated on real activations and weights, which are not available."""
