@@ -210,6 +210,29 @@ int duqpp_fold_smoothing(const float* R, int64_t n_rblocks, const float* lambda,
                          float* R_act, float* R_wgt, void* stream);
 
 /*
+ * Offline: greedy outlier-aware construction of the rotation block that all groups share (Sec. 4.2, paragraph
+ * "Fine-grained Block-diagonal Rotation", steps (1)-(3)).  The paper sketches the construction; the reading built
+ * here: take the block of 32 channels holding the largest |x| of the calibration activations; repeat max_steps
+ * times: find the channel with the largest magnitude, multiply by  E_d . H . diag(1, Q'_t) . E_d  (E_d exchanges
+ * that channel with channel 0, H is the normalised 32 x 32 Sylvester-Hadamard matrix, Q'_t the caller's t-th
+ * orthogonal 31 x 31 draw); keep the product after the step count with the smallest peak |value| (0 steps = the
+ * identity if nothing lowers it).  fp64 in a fixed operation order: the result does not depend on the launch shape.
+ *   x_bf16     in   [T, K] bf16 calibration activations, row stride ldx (elements, multiple of 8), 16-byte aligned
+ *   q_steps    in   [max_steps, 31, 31] fp64, each orthogonal (not checked: it lives on the device)
+ *   max_steps       0 .. 4096 (the paper uses 128)
+ *   R_out      out  [32, 32] fp32, R[r][c] with r the input channel: pass it with n_rblocks = 1
+ *   info       out  2 x int32 on the device: index of the block the matrix was built from, steps kept
+ *   peaks      out  nullable, [max_steps + 1] fp64 on the device: peak |value| after 0, 1, ... steps
+ *   workspace       at least duqpp_construct_rotation_workspace_bytes(T, max_steps) bytes, 256-byte aligned
+ * Enqueues max_steps + 4 kernels on the stream.  Errors as for the other calls.
+ */
+size_t duqpp_construct_rotation_workspace_bytes(int64_t T, int max_steps);   /* host, pure; 0 for invalid arguments */
+int duqpp_construct_rotation(const void* x_bf16, int64_t T, int64_t K, int64_t ldx,
+                             const double* q_steps, int max_steps,
+                             float* R_out, int32_t* info, double* peaks,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * MEASUREMENT ONLY: the rate the chip sustains on the FP4 x FP4 block-scaled matrix instruction of the Eq. 5
  * product alone -- operands in registers, no memory traffic, one wave per SIMD on all 256 CUs, 8 * iters
  * instructions per wave.  Time the call with events: *flops / time is the ceiling of any MXFP4 GEMM at the

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     KERNEL_SMALL,
     gemm_kernel_for,
     DuqppError,
+    construct_rotation,
     fold_smoothing,
     gemm_workspace_bytes,
     lib,

@@ -54,6 +54,10 @@ def _load():
     L.duqpp_rotq_gemm_tiled.argtypes = [vp, i64, fp, i64, u8p, u8p, i64, i64, i64, vp, ci, i64, vp, sz, vp]
     L.duqpp_fold_smoothing.argtypes = [fp, i64, fp, i64, fp, fp, vp]
     L.duqpp_probe_fp4_mfma.argtypes = [u8p, sz, i64, fp, ctypes.POINTER(ctypes.c_double), vp]
+    L.duqpp_construct_rotation_workspace_bytes.argtypes = [i64, ci]
+    L.duqpp_construct_rotation_workspace_bytes.restype = sz
+    L.duqpp_construct_rotation.argtypes = [vp, i64, i64, i64, vp, ci, fp, vp, vp, vp, sz, vp]
+    L.duqpp_construct_rotation.restype = ci
     L.duqpp_probe_fp4_mfma.restype = ci
     for name in ("duqpp_tiled_bytes", "duqpp_tile_operand", "duqpp_untile_operand", "duqpp_quantize_weights_tiled",
                  "duqpp_rotate_quantize_tiled", "duqpp_mxfp4_gemm_tiled", "duqpp_rotq_gemm_tiled",
@@ -336,6 +340,29 @@ def fold_smoothing(R, lam):
     _check(lib.duqpp_fold_smoothing(R.data_ptr(), _n_rblocks(R), lam.data_ptr(), K, R_act.data_ptr(),
                                     R_wgt.data_ptr(), _stream()), "duqpp_fold_smoothing")
     return R_act, R_wgt
+
+
+def construct_rotation(x, q_steps, return_peaks=False, workspace=None):
+    """Greedy construction of the shared rotation block from calibration activations x [T, K] bf16 and the steps'
+    orthogonal draws q_steps [steps, 31, 31] fp64.  Returns (R [1, 32, 32] fp32, block index, steps kept[, peaks])."""
+    _dev(x, torch.bfloat16, "x")
+    _dev(q_steps, torch.float64, "q_steps")
+    if q_steps.dim() != 3 or tuple(q_steps.shape[1:]) != (31, 31) or not q_steps.is_contiguous():
+        raise ValueError("q_steps must be contiguous [steps, 31, 31]")
+    T, K = x.shape
+    steps = q_steps.shape[0]
+    nbytes = lib.duqpp_construct_rotation_workspace_bytes(T, steps)
+    if nbytes == 0:
+        raise ValueError("bad T or number of steps")
+    ws = workspace if workspace is not None else _workspace(nbytes, x.device)[0]
+    R = torch.empty((1, 32, 32), dtype=torch.float32, device=x.device)
+    info = torch.empty(2, dtype=torch.int32, device=x.device)
+    peaks = torch.empty(steps + 1, dtype=torch.float64, device=x.device) if return_peaks else None
+    _check(lib.duqpp_construct_rotation(x.data_ptr(), T, K, x.stride(0), q_steps.data_ptr(), steps, R.data_ptr(),
+                                        info.data_ptr(), peaks.data_ptr() if return_peaks else None, ws.data_ptr(),
+                                        ws.numel(), _stream()), "duqpp_construct_rotation")
+    block, kept = (int(v) for v in info.cpu())
+    return (R, block, kept, peaks) if return_peaks else (R, block, kept)
 
 
 def probe_fp4_mfma(codes, iters, out=None):

@@ -312,6 +312,29 @@ int duqpp_fold_smoothing(const float* R, int64_t n_rblocks, const float* lambda,
     return launch_fold_smoothing(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
 }
 
+size_t duqpp_construct_rotation_workspace_bytes(int64_t T, int max_steps) {
+    if (T < 1 || T > (int64_t)1 << 30 || max_steps < 0 || max_steps > 4096) return 0;
+    return construct_workspace_bytes(T, max_steps);
+}
+
+int duqpp_construct_rotation(const void* x_bf16, int64_t T, int64_t K, int64_t ldx, const double* q_steps,
+                             int max_steps, float* R_out, int32_t* info, double* peaks, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+    if (!x_bf16 || !R_out || !info || (max_steps > 0 && !q_steps)) return DUQPP_ERR_NULL;
+    int st = validate_rows_K(T, K, ldx, 1);
+    if (st != DUQPP_OK) return st;
+    if (max_steps < 0 || max_steps > 4096) return DUQPP_ERR_SHAPE;
+    if (!aligned_to(x_bf16, 16) || (ldx % 8) != 0 || !aligned_to(q_steps, 8) || !aligned_to(R_out, 4) ||
+        !aligned_to(info, 4) || !aligned_to(peaks, 8))
+        return DUQPP_ERR_ALIGN;
+    if (!workspace || workspace_bytes < construct_workspace_bytes(T, max_steps)) return DUQPP_ERR_WORKSPACE;
+    if (!aligned_to(workspace, 256)) return DUQPP_ERR_ALIGN;
+    st = check_device();
+    if (st != DUQPP_OK) return st;
+    ConstructParams p{static_cast<const uint16_t*>(x_bf16), ldx, T, K, q_steps, max_steps, R_out, info, peaks, workspace};
+    return launch_construct_rotation(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
+}
+
 int duqpp_probe_fp4_mfma(const uint8_t* codes, size_t codes_bytes, int64_t iters, float* out, double* flops,
                          void* stream) {
     if (!codes || !out) return DUQPP_ERR_NULL;

@@ -83,6 +83,16 @@ struct FoldParams {
 };
 hipError_t launch_fold_smoothing(const FoldParams& p, hipStream_t stream);
 
+// ---- offline construction of the shared rotation block (construct.hip) ------------------------------
+struct ConstructParams {
+    const uint16_t* x; int64_t ldx; int64_t T; int64_t K;   // calibration activations, bf16 [T, K]
+    const double* q_steps; int steps;                       // [steps][31][31] orthogonal draws
+    float* R_out; int32_t* info; double* peaks;             // [32][32]; {block, steps kept}; nullable [steps + 1]
+    void* workspace;
+};
+size_t construct_workspace_bytes(int64_t T, int steps);
+hipError_t launch_construct_rotation(const ConstructParams& p, hipStream_t stream);
+
 // ---- measurement aid (probe.hip) --------------------------------------------------------------
 struct ProbeParams {
     const uint8_t* codes; int pieces;   // pieces of 2 KiB of code bytes used as operand patterns

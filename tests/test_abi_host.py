@@ -122,6 +122,24 @@ def test_kernel_choice_for_the_benchmark_shapes(lib):
     assert lib.duqpp_mxfp4_gemm_tiled_on(MID, None, P, P, P, 200, 16, 64, P, 0, 16, None) == NULL
 
 
+def test_construct_rotation_host_checks(lib):
+    ws = lib.duqpp_construct_rotation_workspace_bytes
+    assert ws(0, 4) == 0 and ws(8, -1) == 0 and ws(8, 5000) == 0
+    assert ws(100, 128) == 64 + 129 * 256 + 129 * 8192 + 100 * 256
+    c = lib.duqpp_construct_rotation
+    big = 1 << 30
+    assert c(None, 8, 64, 64, P, 2, P, P, None, P, big, None) == NULL
+    assert c(P, 8, 64, 64, None, 2, P, P, None, P, big, None) == NULL
+    assert c(P, 8, 48, 64, P, 2, P, P, None, P, big, None) == SHAPE
+    assert c(P, 8, 64, 64, P, 5000, P, P, None, P, big, None) == SHAPE
+    assert c(P, 8, 64, 60, P, 2, P, P, None, P, big, None) == SHAPE           # stride shorter than a row
+    assert c(P, 8, 64, 68, P, 2, P, P, None, P, big, None) == ALIGN           # stride not a multiple of 8
+    assert c(P, 8, 64, 64, P + 4, 2, P, P, None, P, big, None) == ALIGN
+    assert c(P, 8, 64, 64, P, 2, P, P, None, None, 0, None) == WORKSPACE
+    assert c(P, 8, 64, 64, P, 2, P, P, None, P, 100, None) == WORKSPACE
+    assert c(P, 8, 64, 64, P, 2, P, P, None, P + 16, big, None) == ALIGN
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     import importlib
 
