@@ -52,6 +52,9 @@ def main():
     ap.add_argument("--zero-operands", action="store_true",
                     help="diagnostic, not the metric: time the GEMM on all-zero codes (weights and activations), "
                          "which takes the data-dependent power draw of the matrix cores out of the measurement")
+    ap.add_argument("--construct", action="store_true",
+                    help="time the offline greedy construction of the shared rotation block (128 steps) on the "
+                         "workload's activations and its oracle, print one JSON line, and exit")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the workload, run a plain device copy of known size (256 MiB, 20 times): "
                          "the reference against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -79,6 +82,30 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": {"bytes_read_per_launch": nbytes, "bytes_written_per_launch": nbytes,
                                                "launches": 20}}))
+        return
+    if args.construct:
+        # Offline step, not part of the timed hot path: the calibration batch is the workload's own activations.
+        cfg = wl.CONFIGS[args.config]
+        Tc, Kc = cfg["T"], cfg["K"]
+        xb = wl.make_activations(f"bench-construct-{args.config}", Tc, Kc, cfg["outliers"])
+        q = wl.make_orthogonal_steps(f"bench-construct-{args.config}", 128)
+        x, qd = torch.from_numpy(xb.view(np.int16)).view(torch.bfloat16).to(dev), torch.from_numpy(q).to(dev)
+        duqpp.construct_rotation(x, qd)                     # warm-up
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        R, block, kept, peaks = duqpp.construct_rotation(x, qd, return_peaks=True)
+        torch.cuda.synchronize()
+        gpu_ms = (time.perf_counter() - t0) * 1e3
+        from oracle import construction
+        t0 = time.perf_counter()
+        ref = construction.greedy_rotation(wl.bf16_bits_to_f32(xb), q)
+        cpu_ms = (time.perf_counter() - t0) * 1e3
+        pk = peaks.cpu().numpy()
+        print(json.dumps({"construct_rotation": {
+            "workload": args.config, "T": Tc, "K": Kc, "steps": 128, "ms": round(gpu_ms, 3),
+            "oracle_ms": round(cpu_ms, 1), "block": block, "steps_kept": kept, "peak_before": float(pk[0]),
+            "peak_after": float(pk[kept]), "identical_to_oracle": bool(
+                block == ref["block"] and kept == ref["steps"] and np.array_equal(R.cpu().numpy()[0], ref["R"]))}}))
         return
     # A workload is a list of linears (name, K, N, outliers) run over the same T tokens: one for the single-layer
     # configurations, seven for the decoder-layer set.
