@@ -38,17 +38,27 @@ struct DecStep {
 // a_tile_bytes / a_tile_sbytes: distance between the activations' row tiles (codes / scale words)
 template <int ROWS, int MT>
 __device__ __forceinline__ void dec_load(DecStep<MT>& d, const uint8_t* a_codes, const uint8_t* a_scales,
-                                         int64_t a_tile_bytes, int64_t a_tile_sbytes, int m0, int rta,
+                                         int64_t a_tile_bytes, int64_t a_tile_sbytes, int m0, int rta, int T,
                                          const uint8_t* b_codes, const uint8_t* b_scales, int step, int lane_code,
                                          int lane4, int lane_code_b, int lane4_b, int r) {
     const uint8_t* pb = b_codes + (int64_t)step * 4096 + lane_code_b;
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
-        const int mt = m0 + m < rta ? m0 + m : rta - 1;
-        const uint8_t* pa = a_codes + mt * a_tile_bytes + (int64_t)step * 4096 + lane_code;
+        // Only the lanes of real tokens fetch activations: every workgroup reads the whole activation tile from
+        // L2, which with a handful of tokens would otherwise be more traffic per CU than the weights themselves
+        // (32 rows of mostly padding against ROWS rows of weights).  The other lanes feed zeros; their results
+        // fall on tokens >= T and are dropped.
+        const int mt = m0 + m;
+        if (mt < rta && r < T - 32 * mt) {
+            const uint8_t* pa = a_codes + mt * a_tile_bytes + (int64_t)step * 4096 + lane_code;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) d.a[m][i] = *(const u32x4*)(pa + i * 512);
-        d.sa[m] = *(const uint32_t*)(a_scales + mt * a_tile_sbytes + (int64_t)step * 256 + lane4);
+            for (int i = 0; i < 4; ++i) d.a[m][i] = *(const u32x4*)(pa + i * 512);
+            d.sa[m] = *(const uint32_t*)(a_scales + mt * a_tile_sbytes + (int64_t)step * 256 + lane4);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) d.a[m][i] = u32x4{0u, 0u, 0u, 0u};
+            d.sa[m] = 0x7F7F7F7Fu;
+        }
     }
     // weights are read once; lanes beyond the workgroup's rows load nothing and feed zeros
     if (ROWS == 32 || r < ROWS) {
@@ -87,8 +97,8 @@ __global__ __launch_bounds__(kDecWaves * 64) void gemm_decode_kernel(TiledGemmPa
     const uint8_t* b_codes = p.b_codes + (int64_t)rt * p.GP * 512;
     const uint8_t* b_scales = p.b_scales + (int64_t)rt * NI * 256;
     const int64_t a_tile_bytes = (int64_t)p.GP * 512, a_tile_sbytes = (int64_t)NI * 256;
-    // this workgroup's activation row tiles: MT of them from m0; one past the last tile is replaced by the
-    // last tile (its results fall on tokens >= T and are dropped)
+    // this workgroup's activation row tiles: MT of them from m0; one past the last tile is all zeros
+    // (its results fall on tokens >= T and are dropped)
     const int RTa = (p.T + 31) / 32;
     const int m0 = blockIdx.y * MT;
     // A operand (activations): group 4 g + i of row r sits at (4 g + i) * 512 + r * 16, its scale word at
@@ -106,11 +116,11 @@ __global__ __launch_bounds__(kDecWaves * 64) void gemm_decode_kernel(TiledGemmPa
     // (Deeper register rings measured slower: they cost the occupancy that hides the latency better.)
     DecStep<MT> cur, nxt;
     if (s0 < s1)
-        dec_load<ROWS, MT>(cur, p.a_codes, p.a_scales, a_tile_bytes, a_tile_sbytes, m0, RTa, b_codes, b_scales, s0, lane_code,
+        dec_load<ROWS, MT>(cur, p.a_codes, p.a_scales, a_tile_bytes, a_tile_sbytes, m0, RTa, p.T, b_codes, b_scales, s0, lane_code,
                            lane4, lane_code_b, lane4_b, r);
     for (int s = s0; s < s1; ++s) {
         if (s + 1 < s1)
-            dec_load<ROWS, MT>(nxt, p.a_codes, p.a_scales, a_tile_bytes, a_tile_sbytes, m0, RTa, b_codes, b_scales, s + 1,
+            dec_load<ROWS, MT>(nxt, p.a_codes, p.a_scales, a_tile_bytes, a_tile_sbytes, m0, RTa, p.T, b_codes, b_scales, s + 1,
                                lane_code, lane4, lane_code_b, lane4_b, r);
 #pragma unroll
         for (int m = 0; m < MT; ++m) {
