@@ -492,7 +492,9 @@ void plan_rotq(RotqParams& p) {
     if (groups < 1) groups = 1;
     if (groups > p.ntiles) groups = p.ntiles;
     p.tiles_per_wg = (p.ntiles + groups - 1) / groups;
-    p.ngroups = p.tiled ? groups : (p.ntiles + p.tiles_per_wg - 1) / p.tiles_per_wg;
+    // the fewest runs that keep the longest run as short: 64 tiles over 9 runs are 8 tiles for the longest anyway,
+    // and 8 runs of 8 fetch and split R once less per block pair
+    p.ngroups = (p.ntiles + p.tiles_per_wg - 1) / p.tiles_per_wg;
 }
 
 hipError_t launch_rotq(const RotqParams& p, hipStream_t stream) {
