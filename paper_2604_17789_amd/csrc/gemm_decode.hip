@@ -166,9 +166,12 @@ static void launch_decode_rows(const TiledGemmParams& p, unsigned tiles, unsigne
 hipError_t launch_gemm_decode(const TiledGemmParams& p, hipStream_t stream) {
     if (p.T > kDecodeMaxT) return hipErrorInvalidValue;
     const unsigned tiles = (unsigned)((p.N + 31) / 32);
-    // Measured at N = 4096, K = 14336: halving the row tiles (256 workgroups instead of 128) gains 13 %;
-    // quartering them, 16 waves per workgroup or deeper register rings all lose.
-    const bool cut = tiles < (unsigned)kNumCU;
+    // Measured at N = 4096, K = 14336: with more than a few tokens halving the row tiles (256 workgroups instead
+    // of 128) gains 4 % (T = 16: 9.4 -> 9.0 us); with up to 8 tokens whole tiles win (T = 1: 8.8 -> 8.6 us), as a
+    // half-tile workgroup issues the same loads for half the bytes (K = 4096, N = 14336 forced to half tiles:
+    // 7.1 -> 9.6 us).  Quartering the tiles, 16 waves per workgroup or register rings three and four steps deep
+    // all lose.
+    const bool cut = tiles < (unsigned)kNumCU && p.T > 8;
     // 65..128 tokens: two passes of two row tiles each (blockIdx.y), the weights of the second mostly from cache
     const unsigned passes = p.T <= 64 ? 1u : 2u;
     if (p.T <= 32) {
