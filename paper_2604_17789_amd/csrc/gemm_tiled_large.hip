@@ -210,11 +210,11 @@ __global__ __launch_bounds__(256) void gemm_tiled_large_kernel(TiledGemmParams p
 #define DUQPP_PIN __builtin_amdgcn_sched_barrier(0)
 #define DUQPP_DMA(K) dma_slot(std::integral_constant<int, K>{}); DUQPP_PIN
         // four MFMAs of one row of tile pairs, left to the scheduler (the group barriers below place them)
-#define DUQPP_ROW_FREE(F, I, SEL)                                      \
-        DUQPP_MFMA(acc[I][0], F.a[I], F.b[0], sc.a[I], sc.b[0], SEL);   \
-        DUQPP_MFMA(acc[I][1], F.a[I], F.b[1], sc.a[I], sc.b[1], SEL);   \
-        DUQPP_MFMA(acc[I][2], F.a[I], F.b[2], sc.a[I], sc.b[2], SEL);   \
-        DUQPP_MFMA(acc[I][3], F.a[I], F.b[3], sc.a[I], sc.b[3], SEL)
+#define DUQPP_ROW_FREE(F, I, SEL, J0, J1, J2, J3)                            \
+        DUQPP_MFMA(acc[I][J0], F.a[I], F.b[J0], sc.a[I], sc.b[J0], SEL);   \
+        DUQPP_MFMA(acc[I][J1], F.a[I], F.b[J1], sc.a[I], sc.b[J1], SEL);   \
+        DUQPP_MFMA(acc[I][J2], F.a[I], F.b[J2], sc.a[I], sc.b[J2], SEL);   \
+        DUQPP_MFMA(acc[I][J3], F.a[I], F.b[J3], sc.a[I], sc.b[J3], SEL)
         // ---- first half: groups 2 g of every row tile; the fragments of the second half are read meanwhile
         f1.a[0] = *(const u32x4*)(pa + 512);
         f1.b[0] = *(const u32x4*)(pb + 512);
@@ -227,25 +227,25 @@ __global__ __launch_bounds__(256) void gemm_tiled_large_kernel(TiledGemmParams p
         f1.b[3] = *(const u32x4*)(pb + 3 * kStepBytes + 512); DUQPP_PIN;
         DUQPP_MFMA(acc[0][3], f0.a[0], f0.b[3], sc.a[0], sc.b[3], 0); DUQPP_PIN;
         f1.a[1] = *(const u32x4*)(pa + kStepBytes + 512); DUQPP_PIN;
-        DUQPP_MFMA(acc[1][0], f0.a[1], f0.b[0], sc.a[1], sc.b[0], 0); DUQPP_PIN;
-        f1.a[2] = *(const u32x4*)(pa + 2 * kStepBytes + 512); DUQPP_PIN;
-        DUQPP_MFMA(acc[1][1], f0.a[1], f0.b[1], sc.a[1], sc.b[1], 0); DUQPP_PIN;
-        f1.a[3] = *(const u32x4*)(pa + 3 * kStepBytes + 512); DUQPP_PIN;
-        DUQPP_MFMA(acc[1][2], f0.a[1], f0.b[2], sc.a[1], sc.b[2], 0); DUQPP_PIN;
-        DUQPP_DMA(0);
         DUQPP_MFMA(acc[1][3], f0.a[1], f0.b[3], sc.a[1], sc.b[3], 0); DUQPP_PIN;
+        f1.a[2] = *(const u32x4*)(pa + 2 * kStepBytes + 512); DUQPP_PIN;
+        DUQPP_MFMA(acc[1][2], f0.a[1], f0.b[2], sc.a[1], sc.b[2], 0); DUQPP_PIN;
+        f1.a[3] = *(const u32x4*)(pa + 3 * kStepBytes + 512); DUQPP_PIN;
+        DUQPP_MFMA(acc[1][1], f0.a[1], f0.b[1], sc.a[1], sc.b[1], 0); DUQPP_PIN;
+        DUQPP_DMA(0);
+        DUQPP_MFMA(acc[1][0], f0.a[1], f0.b[0], sc.a[1], sc.b[0], 0); DUQPP_PIN;
         DUQPP_MFMA(acc[2][0], f0.a[2], f0.b[0], sc.a[2], sc.b[0], 0); DUQPP_PIN;
         DUQPP_DMA(1);
         DUQPP_MFMA(acc[2][1], f0.a[2], f0.b[1], sc.a[2], sc.b[1], 0); DUQPP_PIN;
         DUQPP_MFMA(acc[2][2], f0.a[2], f0.b[2], sc.a[2], sc.b[2], 0); DUQPP_PIN;
         DUQPP_DMA(2);
         DUQPP_MFMA(acc[2][3], f0.a[2], f0.b[3], sc.a[2], sc.b[3], 0); DUQPP_PIN;
-        DUQPP_MFMA(acc[3][0], f0.a[3], f0.b[0], sc.a[3], sc.b[0], 0); DUQPP_PIN;
-        DUQPP_DMA(3);
-        DUQPP_MFMA(acc[3][1], f0.a[3], f0.b[1], sc.a[3], sc.b[1], 0); DUQPP_PIN;
-        DUQPP_MFMA(acc[3][2], f0.a[3], f0.b[2], sc.a[3], sc.b[2], 0); DUQPP_PIN;
-        DUQPP_DMA(4);
         DUQPP_MFMA(acc[3][3], f0.a[3], f0.b[3], sc.a[3], sc.b[3], 0); DUQPP_PIN;
+        DUQPP_DMA(3);
+        DUQPP_MFMA(acc[3][2], f0.a[3], f0.b[2], sc.a[3], sc.b[2], 0); DUQPP_PIN;
+        DUQPP_MFMA(acc[3][1], f0.a[3], f0.b[1], sc.a[3], sc.b[1], 0); DUQPP_PIN;
+        DUQPP_DMA(4);
+        DUQPP_MFMA(acc[3][0], f0.a[3], f0.b[0], sc.a[3], sc.b[0], 0); DUQPP_PIN;
         // ---- second half: groups 2 g + 1; the remaining transfers, then the next step's first fragments
         DUQPP_MFMA(acc[0][0], f1.a[0], f1.b[0], sc.a[0], sc.b[0], 1); DUQPP_PIN;
         DUQPP_DMA(5);
@@ -253,13 +253,13 @@ __global__ __launch_bounds__(256) void gemm_tiled_large_kernel(TiledGemmParams p
         DUQPP_MFMA(acc[0][2], f1.a[0], f1.b[2], sc.a[0], sc.b[2], 1); DUQPP_PIN;
         DUQPP_DMA(6);
         DUQPP_MFMA(acc[0][3], f1.a[0], f1.b[3], sc.a[0], sc.b[3], 1); DUQPP_PIN;
-        DUQPP_MFMA(acc[1][0], f1.a[1], f1.b[0], sc.a[1], sc.b[0], 1); DUQPP_PIN;
-        DUQPP_DMA(7);
-        DUQPP_MFMA(acc[1][1], f1.a[1], f1.b[1], sc.a[1], sc.b[1], 1); DUQPP_PIN;
-        DUQPP_DMA(8);
-        DUQPP_MFMA(acc[1][2], f1.a[1], f1.b[2], sc.a[1], sc.b[2], 1); DUQPP_PIN;
-        DUQPP_DMA(9);
         DUQPP_MFMA(acc[1][3], f1.a[1], f1.b[3], sc.a[1], sc.b[3], 1); DUQPP_PIN;
+        DUQPP_DMA(7);
+        DUQPP_MFMA(acc[1][2], f1.a[1], f1.b[2], sc.a[1], sc.b[2], 1); DUQPP_PIN;
+        DUQPP_DMA(8);
+        DUQPP_MFMA(acc[1][1], f1.a[1], f1.b[1], sc.a[1], sc.b[1], 1); DUQPP_PIN;
+        DUQPP_DMA(9);
+        DUQPP_MFMA(acc[1][0], f1.a[1], f1.b[0], sc.a[1], sc.b[0], 1); DUQPP_PIN;
         advance_dma();
         {
             // the next step has landed for this wave, then for all; every LDS read of the current stage has
@@ -278,8 +278,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_large_kernel(TiledGemmParams p
                 sn.b[t] = *(const uint16_t*)(nsb + t * 128);
             }
         }
-        DUQPP_ROW_FREE(f1, 2, 1);
-        DUQPP_ROW_FREE(f1, 3, 1);
+        DUQPP_ROW_FREE(f1, 2, 1, 0, 1, 2, 3);
+        DUQPP_ROW_FREE(f1, 3, 1, 3, 2, 1, 0);
         // the 16 reads above, two at a time ahead of each of the eight MFMAs
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
