@@ -51,16 +51,17 @@ struct Scales {
     uint32_t a[2], b[4];
 };
 
-// the eight MFMAs of one quarter step: groups 4 g + SEL of every row tile pair
+// the eight MFMAs of one quarter step: groups 4 g + SEL of every row tile pair, in an order that changes one
+// operand at a time (the second row runs backwards): operands that switch cost matrix-core time
 #define DUQPP_MFMA8(F, S, SEL)                                    \
     DUQPP_MFMA(acc[0][0], F.a[0], F.b[0], S.a[0], S.b[0], SEL);   \
     DUQPP_MFMA(acc[0][1], F.a[0], F.b[1], S.a[0], S.b[1], SEL);   \
     DUQPP_MFMA(acc[0][2], F.a[0], F.b[2], S.a[0], S.b[2], SEL);   \
     DUQPP_MFMA(acc[0][3], F.a[0], F.b[3], S.a[0], S.b[3], SEL);   \
-    DUQPP_MFMA(acc[1][0], F.a[1], F.b[0], S.a[1], S.b[0], SEL);   \
-    DUQPP_MFMA(acc[1][1], F.a[1], F.b[1], S.a[1], S.b[1], SEL);   \
+    DUQPP_MFMA(acc[1][3], F.a[1], F.b[3], S.a[1], S.b[3], SEL);   \
     DUQPP_MFMA(acc[1][2], F.a[1], F.b[2], S.a[1], S.b[2], SEL);   \
-    DUQPP_MFMA(acc[1][3], F.a[1], F.b[3], S.a[1], S.b[3], SEL)
+    DUQPP_MFMA(acc[1][1], F.a[1], F.b[1], S.a[1], S.b[1], SEL);   \
+    DUQPP_MFMA(acc[1][0], F.a[1], F.b[0], S.a[1], S.b[0], SEL)
 
 // fragments of quarter Q of the stage whose per-lane base addresses are pa (A tiles) and pb (B tiles)
 template <int Q>
@@ -263,12 +264,12 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
         DUQPP_MFMA(acc[0][3], CUR.a[0], CUR.b[3], sc.a[0], sc.b[3], Q); DUQPP_PIN;              \
         DUQPP_DMA(D2);                                                                         \
         NXT.b[3] = *(const u32x4*)(pb + 12288 + (Q + 1) * 512);                                 \
-        DUQPP_MFMA(acc[1][0], CUR.a[1], CUR.b[0], sc.a[1], sc.b[0], Q); DUQPP_PIN;              \
+        DUQPP_MFMA(acc[1][3], CUR.a[1], CUR.b[3], sc.a[1], sc.b[3], Q); DUQPP_PIN;              \
         NXT.a[1] = *(const u32x4*)(pa + 4096 + (Q + 1) * 512);                                  \
-        DUQPP_MFMA(acc[1][1], CUR.a[1], CUR.b[1], sc.a[1], sc.b[1], Q); DUQPP_PIN;              \
+        DUQPP_MFMA(acc[1][2], CUR.a[1], CUR.b[2], sc.a[1], sc.b[2], Q); DUQPP_PIN;              \
         DUQPP_DMA(D3);                                                                         \
-        DUQPP_MFMA(acc[1][2], CUR.a[1], CUR.b[2], sc.a[1], sc.b[2], Q);                         \
-        DUQPP_MFMA(acc[1][3], CUR.a[1], CUR.b[3], sc.a[1], sc.b[3], Q); DUQPP_PIN
+        DUQPP_MFMA(acc[1][1], CUR.a[1], CUR.b[1], sc.a[1], sc.b[1], Q);                         \
+        DUQPP_MFMA(acc[1][0], CUR.a[1], CUR.b[0], sc.a[1], sc.b[0], Q); DUQPP_PIN
         DUQPP_DMA(12);
         DUQPP_QUARTER(0, f0, f1, 0, 1, 2, 3);
         DUQPP_QUARTER(1, f1, f0, 4, 5, 6, 7);
