@@ -122,13 +122,30 @@ def _tiled_path_sampled(name, T, K, N, outliers, w_std, out_dtype, n_rows=48, n_
 
 
 def test_70b_down_proj_full_size():
-    """LLaMA-3-70B down_proj prefill (T=4096, K=28672, N=8192, fp32 out): four tiles per persistent workgroup,
-    112 K steps each."""
+    """LLaMA-3-70B down_proj prefill (T=4096, K=28672, N=8192, fp32 out): 512 tiles of 256 x 256, two per
+    persistent workgroup, 224 K steps each."""
+    import paper_2604_17789_amd as duqpp
     cfg = wl.CONFIGS["c4_70b_down_prefill"]
+    assert duqpp.gemm_kernel_for(cfg["T"], cfg["N"], cfg["K"], duqpp.F32) == duqpp.KERNEL_LARGE
     _tiled_path_sampled("c4", cfg["T"], cfg["K"], cfg["N"], cfg["outliers"], cfg["w_std"], 0, n_rows=32, n_cols=32)
 
 
 def test_layer_set_gate_proj_full_size():
-    """gate_proj of the 8B layer set at T=8192 (K=4096, N=14336, bf16 out): fourteen tiles per persistent
-    workgroup, the transfer pipeline crossing every tile boundary."""
+    """gate_proj of the 8B layer set at T=8192 (K=4096, N=14336, bf16 out): 1792 tiles of 256 x 256, seven per
+    persistent workgroup, the transfer pipeline crossing every tile boundary."""
+    import paper_2604_17789_amd as duqpp
+    assert duqpp.gemm_kernel_for(8192, 14336, 4096, duqpp.BF16) == duqpp.KERNEL_LARGE
     _tiled_path_sampled("c5-gate", 8192, 4096, 14336, (), 0.02, 1)
+
+
+def test_layer_set_down_proj_full_size():
+    """down_proj of the 8B layer set at T=8192 (K=14336, N=4096, bf16 out, outlier channels x100 on its input):
+    the rotate+quantise launch with the most token tiles per wave, 512 tiles of 256 x 256 for the product."""
+    _tiled_path_sampled("c5-down", 8192, 14336, 4096, (wl.OutlierSpec(8, 100.0),), 0.02, 1, n_rows=32, n_cols=32)
+
+
+def test_layer_set_kv_proj_full_size():
+    """k / v projection of the layer set (K=4096, N=1024, bf16 out): one 128 x 256 tile per CU."""
+    import paper_2604_17789_amd as duqpp
+    assert duqpp.gemm_kernel_for(8192, 1024, 4096, duqpp.BF16) == duqpp.KERNEL_MID
+    _tiled_path_sampled("c5-k", 8192, 4096, 1024, (), 0.02, 1, n_rows=32, n_cols=32)
