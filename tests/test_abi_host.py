@@ -148,3 +148,41 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     with pytest.raises(ImportError):
         b._load()
     importlib.reload(b)
+
+
+def test_header_is_plain_c_and_links_from_c(tmp_path):
+    """The boundary is a C ABI: include/duqpp.h compiles as C99 with -pedantic, and a C program linked against
+    the library calls its host-side entry points (no device needed)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    lib_dir = os.path.join(ROOT, "paper_2604_17789_amd")
+    src = tmp_path / "abi.c"
+    calls = ("    typedef void (*fn)(void);\n    fn table[] = {" + ", ".join(f"(fn){name}" for name in _declared_symbols())
+             + "};\n    for (i = 0; i < sizeof table / sizeof table[0]; ++i) if (table[i] == 0) return 100;")
+    src.write_text(f"""
+#include <stdio.h>
+#include <string.h>
+#include "duqpp.h"
+int main(void) {{
+    size_t i;
+{calls}
+    if (strstr(duqpp_version(), "gfx950") == 0) return 1;
+    if (duqpp_gemm_workspace_bytes(64, 4096, 4096, 1) == 0) return 2;
+    if (duqpp_validate_rotate_quantize((const void*)0, 4, 64, 64, (const float*)0, 2, (const uint8_t*)0, (const uint8_t*)0) != DUQPP_ERR_NULL) return 3;
+    if (duqpp_gemm_kernel_for(2048, 4096, 14336, DUQPP_BF16) != DUQPP_GEMM_KERNEL_MID) return 4;
+    if (duqpp_construct_rotation_workspace_bytes(8, 2) == 0) return 5;
+    printf("%s\\n", duqpp_status_string(DUQPP_ERR_WORKSPACE));
+    return 0;
+}}
+""")
+    exe = tmp_path / "abi"
+    cmd = ["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src),
+           "-L", lib_dir, "-lduqpp", "-Wl,-rpath," + lib_dir, "-Wl,-rpath-link,/opt/rocm/lib", "-o", str(exe)]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert res.returncode == 0, res.stdout
+    env = dict(os.environ, LD_LIBRARY_PATH="/opt/rocm/lib:" + os.environ.get("LD_LIBRARY_PATH", ""))
+    run = subprocess.run([str(exe)], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, env=env)
+    assert run.returncode == 0, (run.returncode, run.stdout)
+    assert "workspace" in run.stdout
