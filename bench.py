@@ -298,18 +298,22 @@ def main():
                               "traffic": None}
 
     # ---- what the machine sustains, measured here, beside the published peaks ---------------
-    # FP4 MFMA: the library's register-resident loop on bit patterns of the quantised weights (the clock the chip
-    # settles to depends on the operands); HBM: a plain 1 GiB device copy (reads + writes over time).
+    # FP4 MFMA: the library's register-resident loop on bit patterns of the quantised weights, with every instruction
+    # taking a different operand pair as in the GEMM kernels (the rate depends on how much the operands switch; the
+    # figure with one pair held is kept beside it); HBM: a plain 1 GiB device copy (reads + writes over time).
     if not args.no_machine_probe:
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         pc = sets[0][-1]["bc"]
-        duqpp.probe_fp4_mfma(pc, 2000)
-        torch.cuda.synchronize()
-        e0.record()
-        _, probe_flops = duqpp.probe_fp4_mfma(pc, 6000)
-        e1.record()
-        torch.cuda.synchronize()
-        sustained = probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        rates = {}
+        for switching in (False, True):                     # one operand pair held / a different pair per MFMA
+            duqpp.probe_fp4_mfma(pc, 1000, switching)
+            torch.cuda.synchronize()
+            e0.record()
+            _, probe_flops = duqpp.probe_fp4_mfma(pc, 3000, switching)
+            e1.record()
+            torch.cuda.synchronize()
+            rates[switching] = probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        sustained = rates[True]
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
         dst.copy_(src)
@@ -323,6 +327,7 @@ def main():
         del src, dst
         result["machine"] = {"fp4_mfma_sustained_TFLOP/s": round(sustained, 1),
                              "fp4_mfma_sustained_frac_of_peak": round(sustained / FP4_PEAK_TFLOPS, 4),
+                             "fp4_mfma_held_operands_TFLOP/s": round(rates[False], 1),
                              "hbm_copy_GB/s": round(copy_gbps, 1),
                              "hbm_copy_frac_of_peak": round(copy_gbps / HBM_PEAK_GBPS, 4)}
         if T > 32:

@@ -234,16 +234,20 @@ int duqpp_construct_rotation(const void* x_bf16, int64_t T, int64_t K, int64_t l
 
 /*
  * MEASUREMENT ONLY: the rate the chip sustains on the FP4 x FP4 block-scaled matrix instruction of the Eq. 5
- * product alone -- operands in registers, no memory traffic, one wave per SIMD on all 256 CUs, 8 * iters
- * instructions per wave.  Time the call with events: *flops / time is the ceiling of any MXFP4 GEMM at the
- * clock the chip settles to under this load.
+ * product alone -- operands in registers, no memory traffic, one wave per SIMD on all 256 CUs.  Time the call
+ * with events: *flops / time is the ceiling of any MXFP4 GEMM under this load.
  *   codes   in   at least 2048 bytes (16-byte aligned) of MXFP4 code bytes, used as operand bit patterns
- *                (the power drawn, and so the clock, depends on them)
+ *                (the rate depends on them)
+ *   iters        loop iterations per wave
+ *   switching    0: every instruction takes the same operand pair (8 instructions per iteration);
+ *                1: four activation-side and four weight-side fragments per wave, every instruction a different
+ *                   pair, one operand changing per instruction as in the GEMM kernels (16 per iteration) -- the
+ *                   realistic ceiling, since the rate falls with the switching of the operands
  *   out     out  [256 * 256] fp32 (one value per lane; keeps the work alive)
  *   flops   out  host pointer, nullable: floating-point operations of the launch
  */
-int duqpp_probe_fp4_mfma(const uint8_t* codes, size_t codes_bytes, int64_t iters, float* out, double* flops,
-                         void* stream);
+int duqpp_probe_fp4_mfma(const uint8_t* codes, size_t codes_bytes, int64_t iters, int switching, float* out,
+                         double* flops, void* stream);
 
 /* Host, pure: scratch bytes duqpp_mxfp4_gemm (fused = 0) can use or duqpp_rotq_gemm (fused = 1) needs:
  * room for both operands in the tiled layout.  0 for invalid shapes. */

@@ -335,17 +335,17 @@ int duqpp_construct_rotation(const void* x_bf16, int64_t T, int64_t K, int64_t l
     return launch_construct_rotation(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
 }
 
-int duqpp_probe_fp4_mfma(const uint8_t* codes, size_t codes_bytes, int64_t iters, float* out, double* flops,
-                         void* stream) {
+int duqpp_probe_fp4_mfma(const uint8_t* codes, size_t codes_bytes, int64_t iters, int switching, float* out,
+                         double* flops, void* stream) {
     if (!codes || !out) return DUQPP_ERR_NULL;
-    if (codes_bytes < 2048 || iters < 1 || iters > (int64_t)1 << 24) return DUQPP_ERR_SHAPE;
+    if (codes_bytes < 2048 || iters < 1 || iters > (int64_t)1 << 24 || (switching != 0 && switching != 1)) return DUQPP_ERR_SHAPE;
     if (!aligned_to(codes, 16) || !aligned_to(out, 4)) return DUQPP_ERR_ALIGN;
     int st = check_device();
     if (st != DUQPP_OK) return st;
     size_t pieces = codes_bytes / 2048;
     if (pieces > 4096) pieces = 4096;
-    ProbeParams p{codes, (int)pieces, iters, out};
-    if (flops) *flops = (double)kNumCU * 4.0 * (double)iters * 8.0 * (2.0 * 32 * 32 * 64);
+    ProbeParams p{codes, (int)pieces, iters, switching, out};
+    if (flops) *flops = (double)kNumCU * 4.0 * (double)iters * (switching ? 16.0 : 8.0) * (2.0 * 32 * 32 * 64);
     return launch_probe_fp4_mfma(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
 }
 

@@ -96,7 +96,8 @@ hipError_t launch_construct_rotation(const ConstructParams& p, hipStream_t strea
 // ---- measurement aid (probe.hip) --------------------------------------------------------------
 struct ProbeParams {
     const uint8_t* codes; int pieces;   // pieces of 2 KiB of code bytes used as operand patterns
-    int64_t iters;                      // each wave issues 8 * iters MFMAs
+    int64_t iters;                      // each wave issues 8 * iters MFMAs (16 * iters with switching operands)
+    int switching;                      // 0: one operand pair held; 1: 4 x 4 fragments, a different pair per MFMA
     float* out;                         // [kNumCU * 256]
 };
 hipError_t launch_probe_fp4_mfma(const ProbeParams& p, hipStream_t stream);

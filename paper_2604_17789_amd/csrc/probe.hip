@@ -1,6 +1,9 @@
 // Measurement aid: the rate the chip sustains on the block-scaled FP4 MFMA alone, with operands held in
 // registers -- no memory traffic, no LDS, one wave per SIMD on every CU.  It is the ceiling of any MXFP4 GEMM
-// at the clock the chip settles to under that load, to set beside the nominal peak.
+// under that load, to set beside the nominal peak.  Two patterns: one operand pair held for every instruction,
+// and four activation-side times four weight-side fragments with every instruction taking a different pair in
+// the order of the GEMM kernels' inner loop (one operand changes per instruction).  The second is the honest
+// ceiling: how fast the matrix cores issue depends on how much their operands switch, not only on their values.
 #include "duqpp_internal.h"
 
 namespace duqpp {
@@ -41,8 +44,51 @@ __global__ __launch_bounds__(256) void probe_fp4_mfma_kernel(ProbeParams p) {
     p.out[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// 16 instructions per iteration: acc[i][j] += a[i] . b[j], rows alternately forwards and backwards
+__global__ __launch_bounds__(256) void probe_fp4_mfma_switching_kernel(ProbeParams p) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    i32x8 a[4], b[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int piece = ((blockIdx.x * 4 + wave) * 4 + k) % p.pieces;
+        const u32x4 va = *(const u32x4*)(p.codes + piece * 2048 + lane * 16);
+        const u32x4 vb = *(const u32x4*)(p.codes + piece * 2048 + 1024 + lane * 16);
+        a[k] = i32x8{(int)va[0], (int)va[1], (int)va[2], (int)va[3], 0, 0, 0, 0};
+        b[k] = i32x8{(int)vb[0], (int)vb[1], (int)vb[2], (int)vb[3], 0, 0, 0, 0};
+    }
+    const int sa = 0x7C7E7F80 + (lane & 1), sb = 0x807F7E7D - (lane & 1);
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+#define DUQPP_PROBE_ROW(I, J0, J1, J2, J3, SEL)                                                                    \
+    acc[I][J0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[I], b[J0], acc[I][J0], 4, 4, SEL, sa, SEL, sb); \
+    acc[I][J1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[I], b[J1], acc[I][J1], 4, 4, SEL, sa, SEL, sb); \
+    acc[I][J2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[I], b[J2], acc[I][J2], 4, 4, SEL, sa, SEL, sb); \
+    acc[I][J3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[I], b[J3], acc[I][J3], 4, 4, SEL, sa, SEL, sb)
+    for (int64_t it = 0; it < p.iters; ++it) {
+        DUQPP_PROBE_ROW(0, 0, 1, 2, 3, 0);
+        DUQPP_PROBE_ROW(1, 3, 2, 1, 0, 1);
+        DUQPP_PROBE_ROW(2, 0, 1, 2, 3, 2);
+        DUQPP_PROBE_ROW(3, 3, 2, 1, 0, 3);
+    }
+#undef DUQPP_PROBE_ROW
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s += acc[i][j][e];
+    p.out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 hipError_t launch_probe_fp4_mfma(const ProbeParams& p, hipStream_t stream) {
-    hipLaunchKernelGGL(probe_fp4_mfma_kernel, dim3(kNumCU), dim3(256), 0, stream, p);
+    if (p.switching) hipLaunchKernelGGL(probe_fp4_mfma_switching_kernel, dim3(kNumCU), dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL(probe_fp4_mfma_kernel, dim3(kNumCU), dim3(256), 0, stream, p);
     return hipGetLastError();
 }
 
