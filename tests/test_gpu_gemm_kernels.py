@@ -28,13 +28,13 @@ def _random_mx(rng, rows, K, lo=118, hi=136):
     return codes, scales
 
 
-def _run(env, kernel, ac, asc, bc, bsc, out_dtype=0):
+def _run(env, kernel, ac, asc, bc, bsc, out_dtype=0, out=None):
     torch, duqpp = env
     T, K, N = ac.shape[0], ac.shape[1] * 2, bc.shape[0]
     act, ast = tile_np(ac, asc)
     bct, bst = tile_np(bc, bsc)
     y = duqpp.mxfp4_gemm_tiled(to_dev(act, torch), to_dev(ast, torch), to_dev(bct, torch), to_dev(bst, torch),
-                               T, N, K, out_dtype=out_dtype, kernel=kernel)
+                               T, N, K, out_dtype=out_dtype, kernel=kernel, out=out)
     torch.cuda.synchronize()
     return y
 
@@ -137,3 +137,29 @@ def test_named_kernel_rejections(env):
         _run(env, 9, ac, asc, bc, bsc)
     y = _run(env, LARGE, ac, asc, bc, bsc, 0).cpu().numpy()   # fp32 output is fine
     assert rel_fro(y, linear.mxfp4_gemm(ac, asc, bc, bsc)) <= GEMM_TOL
+
+
+@pytest.mark.parametrize("kernel,T,N,K", [(DECODE, 100, 328, 544), (SMALL, 300, 520, 288), (MID, 300, 520, 288),
+                                          (LARGE, 300, 520, 288)])
+@pytest.mark.parametrize("out_dtype", [0, 1])
+@pytest.mark.parametrize("pad", [8, 3])
+def test_named_kernel_strided_output(env, kernel, T, N, K, out_dtype, pad):
+    """Rows of the result `ldy` = N + pad elements apart: the same values as into a dense result, and nothing
+    written between the rows.  pad = 3 leaves bf16 rows off the 16-byte grid: the 256 x 256 kernel refuses that
+    call, the others store element by element."""
+    torch, duqpp = env
+    rng = np.random.default_rng(kernel * 31 + out_dtype * 7 + pad)
+    ac, asc = _random_mx(rng, T, K)
+    bc, bsc = _random_mx(rng, N, K)
+    print(f"[gemm kernel {NAMES[kernel]}] strided output T={T} N={N} K={K} dtype={out_dtype} ldy=N+{pad}", flush=True)
+    dense = _run(env, kernel, ac, asc, bc, bsc, out_dtype)
+    sentinel = -77.0
+    big = torch.full((T, N + pad), sentinel, dtype=dense.dtype, device=dense.device)
+    if kernel == LARGE and out_dtype == 1 and pad % 8:
+        with pytest.raises(duqpp.DuqppError):
+            _run(env, kernel, ac, asc, bc, bsc, out_dtype, out=big[:, :N])
+        return
+    _run(env, kernel, ac, asc, bc, bsc, out_dtype, out=big[:, :N])
+    assert torch.equal(big[:, :N], dense)
+    assert torch.all(big[:, N:] == sentinel)
+    assert rel_fro(dense.float().cpu().numpy(), linear.mxfp4_gemm(ac, asc, bc, bsc)) <= (GEMM_TOL if out_dtype == 0 else 2.0 ** -8)

@@ -84,6 +84,30 @@ def test_rotate_quantize_tiled(env, T, K):
     assert rotation_error_ratio(yrot.cpu().numpy(), rotation.rotate(xf, R), xf) <= 1e-5
 
 
+@pytest.mark.parametrize("T,K,pad", [(77, 1184, 8), (300, 2048, 4096), (2100, 4096, 64)])
+def test_rotate_quantize_tiled_strided_input(env, T, K, pad):
+    """Token rows `ldx` = K + pad elements apart (a slice of a wider tensor): the same bytes as from dense rows,
+    for the tiled call and for the fused call built on it."""
+    torch, duqpp = env
+    xb = wl.make_activations(f"gpu-rqt-strided-{T}-{K}", T, K + pad, (wl.OutlierSpec(8, 50.0),))
+    R = wl.make_rotation_blocks(f"gpu-rqt-strided-{T}-{K}", K // 32)
+    wide, Rd = to_dev_bf16(xb, torch), to_dev(R, torch)
+    x = wide[:, :K]
+    assert x.stride(0) == K + pad
+    print(f"[rotq tiled] strided input T={T} K={K} ldx={K + pad}", flush=True)
+    ct, st = duqpp.rotate_quantize_tiled(x, Rd)
+    ct_d, st_d = duqpp.rotate_quantize_tiled(x.contiguous(), Rd)
+    torch.cuda.synchronize()
+    assert torch.equal(ct, ct_d) and torch.equal(st, st_d)
+    N = 136
+    wb = wl.make_weights(f"gpu-rqt-strided-{T}-{K}", N, K, 0.02)
+    bct, bst = duqpp.quantize_weights_tiled(to_dev_bf16(wb, torch), Rd)
+    y = duqpp.rotq_gemm_tiled(x, Rd, bct, bst, N)
+    y_d = duqpp.mxfp4_gemm_tiled(ct_d, st_d, bct, bst, T, N, K)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_d)
+
+
 def test_rotate_quantize_tiled_shared_block(env):
     """One rotation block shared by every group (the deployed variant of Sec. 4.2): same result as the
     row-major kernel, which is held to the oracle, and as K/32 copies of the block."""
