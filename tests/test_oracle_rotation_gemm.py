@@ -34,16 +34,21 @@ def test_rotation_direction_and_block_alignment():
 
 
 def test_rotation_exact_rational_brute_force():
-    x = wl.bf16_bits_to_f32(wl.make_activations("rot-bf", 2, 64, (wl.OutlierSpec(1, 1000.0, 1),)))
+    """Against the exact rational dot product: the oracle accumulates in fp64 (error below 32 * 2^-53 of the sum
+    of the terms' magnitudes) and rounds once to fp32 (half an fp32 ulp of the result).  An accumulation in fp32
+    would be off by some 2^-24 of the *terms'* magnitudes, far more wherever the terms cancel."""
+    x = wl.bf16_bits_to_f32(wl.make_activations("rot-bf", 4, 64, (wl.OutlierSpec(1, 1000.0, 1),)))
     R = wl.make_rotation_blocks("rot-bf", 2)
     y = rotation.rotate(x, R)
-    for t in range(2):
+    assert y.dtype == np.float32
+    for t in range(4):
         for j in range(2):
             for c in range(32):
                 exact = sum(_f(x[t, 32 * j + r]) * _f(R[j, r, c]) for r in range(32))
                 ref = float(exact)
                 scale = float(sum(abs(_f(x[t, 32 * j + r]) * _f(R[j, r, c])) for r in range(32)))
-                assert abs(float(y[t, 32 * j + c]) - ref) <= 2.0 ** -23 * scale
+                got = float(y[t, 32 * j + c])
+                assert abs(got - ref) <= 2.0 ** -24 * max(abs(ref), abs(got)) + 2.0 ** -45 * scale
 
 
 def test_rotation_shared_block_equals_repeated_block():
@@ -160,11 +165,13 @@ def _random_mx(rng, rows, K, scale_lo=120, scale_hi=134):
 
 def test_gemm_exact_rational_brute_force_tiny():
     rng = np.random.default_rng(21)
-    T, K, N = 2, 64, 3
+    T, K, N = 3, 128, 4
     ac, asc = _random_mx(rng, T, K)
     bc, bsc = _random_mx(rng, N, K)
     y = linear.mxfp4_gemm(ac, asc, bc, bsc)
-    assert y.shape == (T, N)
+    assert y.shape == (T, N) and y.dtype == np.float64
+    # group sums at exponents up to 28 apart: the results need more than fp32's 24 bits, fp64 holds them exactly
+    assert any(float(np.float32(v)) != float(v) for v in y.flat)
     mags = [Fraction(0), Fraction(1, 2), Fraction(1), Fraction(3, 2), Fraction(2), Fraction(3), Fraction(4), Fraction(6)]
 
     def val(codes, scales, row, k):
@@ -176,7 +183,7 @@ def test_gemm_exact_rational_brute_force_tiny():
     for t in range(T):
         for n in range(N):
             exact = sum(val(ac, asc, t, k) * val(bc, bsc, n, k) for k in range(K))
-            assert y[t, n] == float(exact)          # 64 exact products: the fp64 sum is exact here
+            assert y[t, n] == float(exact)          # 128 exact products within 45 bits of each other: the fp64 sum is exact
 
 
 def test_gemm_integer_case_is_exact():
