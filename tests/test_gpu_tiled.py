@@ -252,6 +252,31 @@ def test_gemm_tiled_scale_bytes_pair_with_their_own_group(env):
     np.testing.assert_array_equal(y, ref.astype(np.float32))   # sums of at most 32 powers of two within 2^17: exact
 
 
+def _edge_shapes():
+    """Seeded draws of T and N from the values either side of every tile edge of the four kernels (32, 64, 128,
+    256 and their multiples), K from 1 to 80 groups."""
+    rng = np.random.default_rng(20260417)
+    edges = [1, 2, 31, 32, 33, 63, 64, 65, 95, 97, 127, 128, 129, 191, 193, 255, 256, 257, 300, 383, 385, 511, 512,
+             513, 640, 767, 769]
+    shapes = []
+    for _ in range(28):
+        shapes.append((int(rng.choice(edges)), int(rng.choice(edges)), 32 * int(rng.integers(1, 81))))
+    return shapes
+
+
+@pytest.mark.parametrize("T,N,K", _edge_shapes())
+def test_gemm_tiled_shapes_at_tile_edges(env, T, N, K):
+    """Whatever kernel the library picks for the shape: the product against the oracle, and the bf16 result as
+    the rounding of the fp32 one."""
+    rng = np.random.default_rng(T * 7919 + N * 104729 + K)
+    ac, asc = _random_mx(rng, T, K)
+    bc, bsc = _random_mx(rng, N, K)
+    print(f"[gemm tiled] tile edges T={T} N={N} K={K}", flush=True)
+    y32 = _gemm_tiled(env, ac, asc, bc, bsc, 0).cpu().numpy()
+    assert rel_fro(y32, linear.mxfp4_gemm(ac, asc, bc, bsc)) <= GEMM_TOL
+    np.testing.assert_array_equal(bf16_dev_to_bits(_gemm_tiled(env, ac, asc, bc, bsc, 1)), linear.round_to_bf16_bits(y32))
+
+
 @pytest.mark.parametrize("T,N,K", [(70, 200, 1024), (1100, 8300, 544), (2100, 4200, 32)])
 def test_gemm_tiled_bf16_output(env, T, N, K):
     rng = np.random.default_rng(14)
