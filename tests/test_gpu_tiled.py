@@ -84,6 +84,40 @@ def test_rotate_quantize_tiled(env, T, K):
     assert rotation_error_ratio(yrot.cpu().numpy(), rotation.rotate(xf, R), xf) <= 1e-5
 
 
+def _rotq_edge_shapes():
+    """Seeded draws: token counts either side of the 32-token tile edges and of the launch plan's changes of
+    shape, group counts that are odd, not multiples of 8 (padded groups) or of 16 (a workgroup's column chunk)."""
+    rng = np.random.default_rng(4172026)
+    tokens = [1, 2, 31, 32, 33, 63, 64, 65, 127, 129, 255, 257, 300, 511, 513, 1000]
+    groups = [1, 2, 3, 7, 8, 9, 15, 16, 17, 31, 33, 37, 63, 65, 100, 129]
+    return [(int(rng.choice(tokens)), 32 * int(rng.choice(groups)), int(rng.integers(0, 2))) for _ in range(20)]
+
+
+@pytest.mark.parametrize("T,K,shared", _rotq_edge_shapes())
+def test_rotate_quantize_shapes_at_tile_edges(env, T, K, shared):
+    """Both layouts from the same rotated values: codes and scales bit-exact against the oracle's quantiser on the
+    values the row-major call reports, the tiled call's bytes in their tiled positions with the documented padding,
+    the rotation within tolerance."""
+    torch, duqpp = env
+    name = f"gpu-rq-edge-{T}-{K}-{shared}"
+    xb = wl.make_activations(name, T, K, (wl.OutlierSpec(min(4, K // 8), 50.0), wl.OutlierSpec(1, 1000.0, 1)))
+    R = wl.make_rotation_blocks(name, 1 if shared else K // 32)
+    x, Rd = to_dev_bf16(xb, torch), to_dev(R, torch)
+    print(f"[rotq] tile edges T={T} K={K} shared={shared}", flush=True)
+    ct, st = duqpp.rotate_quantize_tiled(x, Rd)
+    c_rm, s_rm, yrot = duqpp.rotate_quantize(x, Rd, return_rotated=True)
+    torch.cuda.synchronize()
+    codes, scales, pc, ps = untile_np(ct.cpu().numpy(), st.cpu().numpy(), T, K)
+    assert np.all(pc == 0) and np.all(ps == 127)
+    c_ref, s_ref = mxfp4.quantize(yrot.cpu().numpy())
+    np.testing.assert_array_equal(c_rm.cpu().numpy(), c_ref)
+    np.testing.assert_array_equal(s_rm.cpu().numpy(), s_ref)
+    np.testing.assert_array_equal(codes, c_ref)
+    np.testing.assert_array_equal(scales, s_ref)
+    xf = wl.bf16_bits_to_f32(xb)
+    assert rotation_error_ratio(yrot.cpu().numpy(), rotation.rotate(xf, R), xf) <= 1e-5
+
+
 @pytest.mark.parametrize("T,K,pad", [(77, 1184, 8), (300, 2048, 4096), (2100, 4096, 64)])
 def test_rotate_quantize_tiled_strided_input(env, T, K, pad):
     """Token rows `ldx` = K + pad elements apart (a slice of a wider tensor): the same bytes as from dense rows,
