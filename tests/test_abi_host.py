@@ -186,3 +186,15 @@ int main(void) {{
     run = subprocess.run([str(exe)], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, env=env)
     assert run.returncode == 0, (run.returncode, run.stdout)
     assert "workspace" in run.stdout
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The bench measures one GPU's share; asked for more it says so and exits before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], stdout=subprocess.PIPE,
+                       stderr=subprocess.PIPE, text=True, timeout=300)
+    assert p.returncode != 0
+    assert "one GPU" in (p.stdout + p.stderr)
+    assert "{" not in p.stdout                               # no result line
