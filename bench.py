@@ -113,7 +113,9 @@ def main():
         cfg = wl.LAYER_SET_CONFIGS[args.config]
         linears = [(nm, k, n, cfg["outliers"] if has else ()) for nm, k, n, has in cfg["layers"]]
         if args.sets == 8:
-            args.sets = 2                                   # 1.3 GB of activations per set: two already exceed the cache
+            # 0.64 GB of activations per set; four, so that the per-linear loops below (one linear's buffers of
+            # every set: 4 x 85 MB for the 4096-wide ones) also cycle more than the 256 MB last-level cache holds
+            args.sets = 4
     else:
         cfg = wl.CONFIGS[args.config]
         linears = [("linear", cfg["K"], cfg["N"], cfg["outliers"])]
@@ -290,6 +292,9 @@ def main():
     }
     if per_linear:
         result["components"]["per_linear"] = per_linear
+        # each per-linear loop cycles the buffer sets of ONE linear; the aggregate figures above cycle all of them
+        result["components"]["per_linear_note"] = (f"each figure cycles one linear's {nsets} buffer sets; with fewer than "
+                                                   "4 sets of a 4096-wide linear they fit the 256 MB last-level cache")
     if T <= 32:
         # decode shapes: the product streams the weights once, so HBM bounds it, not the matrix cores
         result["roofline"] = {"kernel": "mxfp4_gemm (decode)", "bound": "hbm",

@@ -330,7 +330,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_large_kernel(TiledGemmParams p
                         const u32x4 v = *(const u32x4*)(rp + 8 * k * kEpPitch);
                         const int grow = m0 + 32 * i + 8 * k + (lane >> 3);
                         if (grow < p.T && gcol + 64 * hh < p.N)
-                            *(u32x4*)(dst0 + (int64_t)(32 * i + 8 * k) * p.ldy + 64 * hh) = v;
+                            // streamed: the result is not read again here, the operands' lines are (2-3 % at T = 8192)
+                            __builtin_nontemporal_store(v, (u32x4*)(dst0 + (int64_t)(32 * i + 8 * k) * p.ldy + 64 * hh));
                     }
                 }
             }
