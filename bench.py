@@ -27,7 +27,7 @@ FP4_PEAK_TFLOPS = 10100.0     # MI355X dense MXFP4 matrix peak, published (256 C
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE (x 2.000) + WRITE_SIZE (x 1.000), the factors a plain
 # 256 MiB device copy gives for the same counters; workload c2_8b_down_prefill
 # (profiles/gemm_tiled_and_rotq_c2_8b_down_prefill_hbm_traffic.md).
-MEASURED_TRAFFIC = {"gemm": 125.13e6 + 16.78e6, "rotq": 61.12e6 + 15.60e6}
+MEASURED_TRAFFIC = {"gemm": 125.12e6 + 16.79e6, "rotq": 60.93e6 + 15.60e6}
 
 
 def rotq_algorithmic_bytes(T, K):
