@@ -242,6 +242,13 @@ GEMM_SHAPES = [
     (2100, 4200, 32),     # 17 x 17 = 289 tiles of a single K step each
     (3000, 5000, 288),    # 24 x 20 = 480 tiles, two K steps (the second mostly padding)
     (700, 40000, 256),    # 6 x 157 = 942 tiles: up to four tiles per workgroup, one K step
+    # the 16-row weight-streaming kernel (up to 16 tokens, fewer than 256 weight row tiles)
+    (16, 40, 256),        # one K step: seven of the eight waves have none; second row tile with 8 real rows
+    (9, 17, 32),          # a single group; tokens and channels both short of 16
+    (13, 300, 14368),     # 57 K steps over eight waves: 8, 8, ..., 1 steps (even and odd runs of the two-set loop)
+    (16, 8160, 64),       # 255 row tiles, the most this kernel takes
+    (1, 4100, 14336),     # the LLaMA-3-8B down_proj decode shape, ragged in N
+    (16, 8192, 64),       # 256 row tiles: back on the 32-row kernel
 ]
 
 
@@ -309,6 +316,36 @@ def test_gemm_tiled_shapes_at_tile_edges(env, T, N, K):
     y32 = _gemm_tiled(env, ac, asc, bc, bsc, 0).cpu().numpy()
     assert rel_fro(y32, linear.mxfp4_gemm(ac, asc, bc, bsc)) <= GEMM_TOL
     np.testing.assert_array_equal(bf16_dev_to_bits(_gemm_tiled(env, ac, asc, bc, bsc, 1)), linear.round_to_bf16_bits(y32))
+
+
+@pytest.mark.parametrize("T", [1, 7, 16])
+def test_gemm_tiled_16_row_kernel_exact_cases(env, T):
+    """Up to 16 tokens against fewer than 256 weight row tiles: the 16-row kernel.  Equal scales make every partial
+    sum exact (bit-identical to the oracle in any order); then one non-zero element per group with scales that differ
+    from group to group and row to row, where a scale byte taken from the wrong group, row or operand shows."""
+    rng = np.random.default_rng(160 + T)
+    N, K = 330, 14336
+    ac = rng.integers(0, 256, size=(T, K // 2)).astype(np.uint8)
+    bc = rng.integers(0, 256, size=(N, K // 2)).astype(np.uint8)
+    asc = np.full((T, K // 32), 125, dtype=np.uint8)
+    bsc = np.full((N, K // 32), 131, dtype=np.uint8)
+    y = _gemm_tiled(env, ac, asc, bc, bsc).cpu().numpy()
+    np.testing.assert_array_equal(y, linear.mxfp4_gemm(ac, asc, bc, bsc).astype(np.float32))
+    K = 1024
+    G = K // 32
+    ac = np.zeros((T, K // 2), dtype=np.uint8)
+    bc = np.zeros((N, K // 2), dtype=np.uint8)
+    pos = rng.integers(0, 32, size=G)
+    for j in range(G):
+        k = 32 * j + int(pos[j])
+        ac[:, k // 2] = 0x02 << (4 * (k & 1))
+        bc[:, k // 2] = 0x02 << (4 * (k & 1))
+    asc = (110 + (np.arange(T)[:, None] * 7 + np.arange(G)[None, :] * 3) % 9).astype(np.uint8)
+    bsc = (120 + (np.arange(N)[:, None] * 5 + np.arange(G)[None, :]) % 8).astype(np.uint8)
+    y = _gemm_tiled(env, ac, asc, bc, bsc).cpu().numpy()
+    np.testing.assert_array_equal(y, linear.mxfp4_gemm(ac, asc, bc, bsc).astype(np.float32))
+    y16 = bf16_dev_to_bits(_gemm_tiled(env, ac, asc, bc, bsc, 1))
+    np.testing.assert_array_equal(y16, linear.round_to_bf16_bits(y))
 
 
 @pytest.mark.parametrize("T,N,K", [(70, 200, 1024), (1100, 8300, 544), (2100, 4200, 32)])
