@@ -411,10 +411,20 @@ hipError_t launch_gemm_tiled_mid(const TiledGemmParams& p, hipStream_t stream) {
 
 // Which kernel runs a shape.
 int choose_gemm_kernel(const TiledGemmParams& p) {
-    // Weight-streaming shapes go to the decode kernel: always up to 64 tokens; from 65 to 128 (two passes
+    // Weight-streaming shapes go to the decode kernel: always up to 32 tokens, up to 64 unless the 64 x 128 tiles fill
+    // the chip (N beyond about 24 k); from 65 to 128 (two passes
     // over the weights) when that beats the 128 x 256 kernel, which then has at most N / 256 of the 256 CUs busy
     // for GP / 8 steps of about a microsecond.  Times in microseconds, fitted to measurements at the LLaMA-3-8B shapes.
-    if (p.T <= 64) return DUQPP_GEMM_KERNEL_DECODE;
+    if (p.T <= 32) return DUQPP_GEMM_KERNEL_DECODE;
+    if (p.T <= 64) {
+        // Two activation row tiles per wave stream the weights at about 4 TB/s; the 64 x 128 tiles take about 0.8 us
+        // per K step of 256 once there are enough of them for every CU, whatever the byte count (N = 28672, K = 8192,
+        // T = 48: 27.9 us against 33.9 us; N = 14336, K = 4096: 12.1 us against 11.1 us).
+        const double t_decode = 2.5 + (double)p.N * p.GP * 17.0 / 4.0e6;
+        const int64_t small_tiles = (int64_t)((p.T + 63) / 64) * ((p.N + 127) / 128);
+        const double t_small = 2.5 + 0.8 * (p.GP / 8) * (double)((small_tiles + 2 * kNumCU - 1) / (2 * kNumCU));
+        return t_decode <= t_small ? DUQPP_GEMM_KERNEL_DECODE : DUQPP_GEMM_KERNEL_SMALL;
+    }
     const int64_t mid_tiles = (int64_t)((p.T + kBM - 1) / kBM) * ((p.N + kBN - 1) / kBN);
     if (p.T <= kDecodeMaxT) {
         const double weight_bytes = (double)p.N * p.GP * 17.0;

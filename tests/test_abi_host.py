@@ -106,6 +106,8 @@ def test_kernel_choice_for_the_benchmark_shapes(lib):
     k = lib.duqpp_gemm_kernel_for
     assert k(64, 4096, 4096, F32) == DECODE                # q_proj reference shape
     assert k(1, 14336, 4096, F32) == DECODE and k(16, 4096, 14336, F32) == DECODE
+    assert k(48, 14336, 4096, BF16) == DECODE and k(64, 8192, 28672, F32) == DECODE
+    assert k(48, 28672, 8192, BF16) == SMALL and k(32, 28672, 8192, BF16) == DECODE   # 224 tiles of 64 x 128 fill the chip
     assert k(512, 4096, 4096, BF16) == SMALL               # 64 tiles of 128 x 256
     assert k(2048, 4096, 14336, BF16) == MID               # 8B down_proj prefill: 256 tiles of 128 x 256, 128 of 256 x 256
     assert k(8192, 1024, 4096, BF16) == MID                # k / v projections of the layer set

@@ -249,6 +249,7 @@ GEMM_SHAPES = [
     (16, 8160, 64),       # 255 row tiles, the most this kernel takes
     (1, 4100, 14336),     # the LLaMA-3-8B down_proj decode shape, ragged in N
     (16, 8192, 64),       # 256 row tiles: back on the 32-row kernel
+    (48, 28672, 288),     # 33-64 tokens against so many channels that the 64 x 128 tiles are chosen over weight streaming
 ]
 
 
