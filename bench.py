@@ -245,6 +245,7 @@ def main():
                 with torch.cuda.graph(g, stream=sg):
                     sr.wait_stream(sg)
                     free = {}                              # (set, linear) -> event after the GEMM that last read its codes
+                    events = []                            # every event stays alive until the capture has ended
                     for i in range(args.steps):
                         k = i % nsets
                         for li, l in enumerate(sets[k]):
@@ -258,6 +259,7 @@ def main():
                             gemm1(l)
                             free[(k, li)] = torch.cuda.Event()
                             free[(k, li)].record(sg)
+                            events += [ready, free[(k, li)]]
                     sg.wait_stream(sr)
             torch.cuda.synchronize()
             g.replay()

@@ -490,6 +490,7 @@ def test_two_stream_graph_matches_eager_launches(env):
         with torch.cuda.graph(g, stream=sg):
             sr.wait_stream(sg)
             free = {}
+            events = []                                    # kept alive until the capture has ended
             for i in range(steps):
                 k = i % nsets
                 with torch.cuda.stream(sr):
@@ -502,6 +503,7 @@ def test_two_stream_graph_matches_eager_launches(env):
                 gm(sets[k])
                 free[k] = torch.cuda.Event()
                 free[k].record(sg)
+                events += [ready, free[k]]
             sg.wait_stream(sr)
     torch.cuda.synchronize()
     for rep in range(3):
