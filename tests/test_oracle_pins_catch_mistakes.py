@@ -66,6 +66,15 @@ MISTAKES = [
      [("r = u + 0x7FFF + ((u >> 16) & 1)", "r = u + 0x8000")]),
     ("weights divided by Lambda instead of multiplied", "pipeline.py",
      [("w = smoothing.apply(w, lam, inverse=False)", "w = smoothing.apply(w, lam, inverse=True)")]),
+    ("group error statistic: squared norms (no square root)", "pipeline.py",
+     [("return float(np.mean(num[ok] / den[ok]))", "return float(np.mean((num[ok] / den[ok]) ** 2))")]),
+    ("group error statistic: normalised by the quantised group instead of the group itself", "pipeline.py",
+     [("den = np.linalg.norm(y.reshape(y.shape[0], G, 32), axis=-1)",
+       "den = np.linalg.norm((d + y).reshape(y.shape[0], G, 32), axis=-1)")]),
+    ("group error statistic: ratio of whole-tensor norms instead of the mean of per-group ratios", "pipeline.py",
+     [("return float(np.mean(num[ok] / den[ok]))", "return float(np.linalg.norm(num[ok]) / np.linalg.norm(den[ok]))")]),
+    ("group error statistic: groups without norm counted in the mean", "pipeline.py",
+     [("return float(np.mean(num[ok] / den[ok]))", "return float(np.sum(num[ok] / den[ok]) / ok.size)")]),
 ]
 
 

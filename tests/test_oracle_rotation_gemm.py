@@ -156,6 +156,53 @@ def test_rotation_lowers_group_error_on_outlier_groups():
     assert after < before
 
 
+def _worked_group_errors():
+    """(group values, hand-worked squared error norm, hand-worked squared norm) of tests/golden/group_error_worked.txt,
+    the group values taken from the worked groups of Eq. 2 by name."""
+    import os
+    here = os.path.dirname(__file__)
+    groups = {}
+    for line in open(os.path.join(here, "golden", "mxfp4_worked_groups.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        parts = [p.strip() for p in line.split(";")]
+        x = np.full(32, float(parts[2][5:]) if parts[2].startswith("fill=") else 0.0, dtype=np.float32)
+        vals = [float(v) for v in parts[1].split(",")]
+        x[:len(vals)] = vals
+        groups[parts[0]] = x
+    out = []
+    for line in open(os.path.join(here, "golden", "group_error_worked.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, num, den = [p.strip() for p in line.split(";")]
+        out.append((groups[name], float(num), float(den)))
+    return out
+
+
+def test_group_error_statistic_on_hand_worked_groups():
+    """The statistic of Sec. 4.1 (caption of Fig. 1): per group ||Q(x) - x||_2 / ||x||_2, then the mean over groups.
+    Each worked group alone, then all of them side by side in two rows with an all-zero group between them (a group
+    without norm has no ratio and is left out of the mean).  A squared norm, the norm of Q(x) in the denominator, a
+    ratio of whole-tensor norms or a mean that counts the empty group all miss these values."""
+    worked = _worked_group_errors()
+    assert len(worked) == 4
+    ratios = []
+    for x, num, den in worked:
+        c, s = mxfp4.quantize(x.reshape(1, 32))
+        r = pipeline.per_group_normalised_error(x.reshape(1, 32), c, s)
+        assert abs(r - (num / den) ** 0.5) <= 1e-7, (r, num, den)
+        ratios.append((num / den) ** 0.5)
+    assert ratios[0] < 0.06 < 0.14 < ratios[1] < 0.15 < 0.19 < ratios[2] < 0.2 and ratios[3] == 0.0
+    z = np.zeros(32, dtype=np.float32)
+    rows = np.stack([np.concatenate([worked[0][0], z, worked[1][0]]),
+                     np.concatenate([worked[2][0], worked[3][0], z])])
+    c, s = mxfp4.quantize(rows)
+    got = pipeline.per_group_normalised_error(rows, c, s)
+    assert abs(got - sum(ratios) / 4.0) <= 1e-7
+
+
 # ---------------------------------------------------------------- GEMM
 def _random_mx(rng, rows, K, scale_lo=120, scale_hi=134):
     codes = rng.integers(0, 256, size=(rows, K // 2)).astype(np.uint8)
