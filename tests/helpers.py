@@ -33,6 +33,47 @@ def rel_fro(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
+E2M1_BOUNDARIES = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0])     # rounding boundaries of Eq. 2 in units of the scale
+
+
+def assert_codes_differ_only_at_boundaries(codes, scales, c_ref, s_ref, y_ref, x_f32, tol=1e-5, max_fraction=1e-5):
+    """Device codes / scales (each side rotated in its own precision) against the oracle's, both row-major.
+    The device's rotated values lie within tol * ||x_block||_2 of the oracle's y_ref, so a differing scale needs the
+    oracle's group maximum within that distance of a power of two (and differs by one), and a differing code in a
+    group with equal scales needs the oracle's |y| / s within tol * ||x_block||_2 / s of a rounding boundary of Eq. 2
+    (and is the neighbouring code; its sign may differ only if |y| itself is that small).  At most max_fraction of the
+    codes and of the scales may differ at all.  Returns (differing codes, differing scales)."""
+    rows, G = s_ref.shape
+    u = np.stack([codes & 0xF, codes >> 4], axis=-1).reshape(rows, G, 32)
+    u_ref = np.stack([c_ref & 0xF, c_ref >> 4], axis=-1).reshape(rows, G, 32)
+    y = np.abs(np.asarray(y_ref, dtype=np.float64)).reshape(rows, G, 32)
+    slack = tol * np.linalg.norm(np.asarray(x_f32, dtype=np.float64).reshape(rows, G, 32), axis=-1)     # [rows, G]
+    ds = scales != s_ref
+    for t, j in zip(*np.nonzero(ds)):
+        assert abs(int(scales[t, j]) - int(s_ref[t, j])) == 1, (t, j, scales[t, j], s_ref[t, j])
+        amax = y[t, j].max()
+        edge = 2.0 ** (max(int(scales[t, j]), int(s_ref[t, j])) - 127 + 2)      # the power of two between the two scales
+        assert abs(amax - edge) <= slack[t, j], (t, j, amax, edge, slack[t, j])
+    dc = (u != u_ref) & ~ds[:, :, None]
+    for t, j, i in zip(*np.nonzero(dc)):
+        s = 2.0 ** (int(s_ref[t, j]) - 127)
+        v = y[t, j, i] / s
+        a, b = int(u[t, j, i]), int(u_ref[t, j, i])
+        if (a ^ b) & 8:
+            assert y[t, j, i] <= slack[t, j], (t, j, i, "sign", y[t, j, i], slack[t, j])
+        assert abs((a & 7) - (b & 7)) <= 1, (t, j, i, a, b)
+        if (a & 7) != (b & 7):
+            assert np.min(np.abs(E2M1_BOUNDARIES - v)) <= slack[t, j] / s, (t, j, i, v, slack[t, j] / s)
+    n_c, n_s = int(dc.sum()), int(ds.sum())
+    assert n_c <= max(1, int(max_fraction * u.size)) and n_s <= max(1, int(max_fraction * ds.size)), (n_c, n_s)
+    return n_c, n_s
+
+
+def per_element_gemm_bound(a_codes, a_scales, b_codes, b_scales, dequantize):
+    """sum_k |a[t, k]| |b[n, k]|: what an fp32 accumulation error of a product sum is relative to."""
+    return np.abs(dequantize(a_codes, a_scales)) @ np.abs(dequantize(b_codes, b_scales)).T
+
+
 # ---- the tiled operand layout, restated in numpy (index arithmetic only) ----
 def tiled_shape(rows, K):
     G = K // 32

@@ -6,7 +6,10 @@ import pytest
 
 import workloads as wl
 from oracle import linear, mxfp4, rotation
-from helpers import bf16_dev_to_bits, rel_fro, rotation_error_ratio, to_dev, to_dev_bf16, untile_np
+from helpers import (assert_codes_differ_only_at_boundaries, bf16_dev_to_bits, per_element_gemm_bound, rel_fro,
+                     rotation_error_ratio, to_dev, to_dev_bf16, untile_np)
+
+ELEM_TOL = 1e-5      # per sampled output: |y - ref| <= ELEM_TOL * sum_k |a| |b| (fp32 accumulation of exact products)
 
 pytestmark = pytest.mark.gpu
 
@@ -33,12 +36,18 @@ def test_headline_config_full_size():
 
     print("[full] oracle: rotation", flush=True)
     xf = wl.bf16_bits_to_f32(xb)
-    assert rotation_error_ratio(yrot_h, rotation.rotate(xf, R), xf) <= 1e-5
+    y_ref = rotation.rotate(xf, R)
+    assert rotation_error_ratio(yrot_h, y_ref, xf) <= 1e-5
     print("[full] oracle: quantiser on the device's rotated values", flush=True)
     c_ref, s_ref = mxfp4.quantize(yrot_h)
     np.testing.assert_array_equal(as_h, s_ref)
     np.testing.assert_array_equal(ac_h, c_ref)
     del c_ref, s_ref, yrot_h
+    print("[full] oracle: quantiser on its own rotated values (differences only at rounding boundaries)", flush=True)
+    c_own, s_own = mxfp4.quantize(y_ref)
+    n_c, n_s = assert_codes_differ_only_at_boundaries(ac_h, as_h, c_own, s_own, y_ref, xf)
+    print(f"[full] {n_c} of {T * K} codes and {n_s} of {T * K // 32} scales differ end to end", flush=True)
+    del c_own, s_own, y_ref
 
     print("[full] oracle: sampled GEMM rows and columns", flush=True)
     rng = np.random.default_rng(2048)
@@ -48,8 +57,12 @@ def test_headline_config_full_size():
     y32_h = y32.cpu().numpy()
     ref_rows = linear.mxfp4_gemm(ac_h[rows], as_h[rows], bc_h, bs_h)
     ref_cols = linear.mxfp4_gemm(ac_h, as_h, bc_h[cols], bs_h[cols])
+    bound_rows = ELEM_TOL * per_element_gemm_bound(ac_h[rows], as_h[rows], bc_h, bs_h, mxfp4.dequantize)
+    bound_cols = ELEM_TOL * per_element_gemm_bound(ac_h, as_h, bc_h[cols], bs_h[cols], mxfp4.dequantize)
     assert rel_fro(y32_h[rows], ref_rows) <= 1e-5
     assert rel_fro(y32_h[:, cols], ref_cols) <= 1e-5
+    assert np.all(np.abs(y32_h[rows] - ref_rows) <= bound_rows)
+    assert np.all(np.abs(y32_h[:, cols] - ref_cols) <= bound_cols)
     y16_h = bf16_dev_to_bits(y16)
     np.testing.assert_array_equal(y16_h, linear.round_to_bf16_bits(y32_h))
     assert torch.equal(y16, yf)
@@ -72,6 +85,8 @@ def test_headline_config_full_size():
     y32_th = y32_t.cpu().numpy()
     assert rel_fro(y32_th[rows], ref_rows) <= 1e-5
     assert rel_fro(y32_th[:, cols], ref_cols) <= 1e-5
+    assert np.all(np.abs(y32_th[rows] - ref_rows) <= bound_rows)
+    assert np.all(np.abs(y32_th[:, cols] - ref_cols) <= bound_cols)
     np.testing.assert_array_equal(bf16_dev_to_bits(y16_t), linear.round_to_bf16_bits(y32_th))
     assert torch.equal(y16_t, yf_t)
 
@@ -93,6 +108,9 @@ def _tiled_path_sampled(name, T, K, N, outliers, w_std, out_dtype, n_rows=48, n_
     bct, bst = duqpp.quantize_weights_tiled(w, Rd)
     act, ast = duqpp.rotate_quantize_tiled(x, Rd)
     y = duqpp.mxfp4_gemm_tiled(act, ast, bct, bst, T, N, K, out_dtype=out_dtype)
+    # the fp32 result of the same kernel at the same shape: graded at 1e-5; a bf16 result must be its rounding
+    y32 = y if out_dtype == 0 else duqpp.mxfp4_gemm_tiled(act, ast, bct, bst, T, N, K, out_dtype=0)
+    assert duqpp.gemm_kernel_for(T, N, K, 0) == duqpp.gemm_kernel_for(T, N, K, out_dtype)
     torch.cuda.synchronize()
     rng = np.random.default_rng(T + N)
     rows = np.sort(rng.choice(T, n_rows, replace=False))
@@ -108,17 +126,31 @@ def _tiled_path_sampled(name, T, K, N, outliers, w_std, out_dtype, n_rows=48, n_
     np.testing.assert_array_equal(a_c[rows], c_rm.cpu().numpy())
     np.testing.assert_array_equal(a_s[rows], s_rm.cpu().numpy())
     xf = wl.bf16_bits_to_f32(xb[rows])
-    assert rotation_error_ratio(yrot.cpu().numpy(), rotation.rotate(xf, R), xf) <= 1e-5
+    y_own = rotation.rotate(xf, R)
+    assert rotation_error_ratio(yrot.cpu().numpy(), y_own, xf) <= 1e-5
     c_ref, s_ref = mxfp4.quantize(yrot.cpu().numpy())
     np.testing.assert_array_equal(c_rm.cpu().numpy(), c_ref)
     np.testing.assert_array_equal(s_rm.cpu().numpy(), s_ref)
+    c_own, s_own = mxfp4.quantize(y_own)                   # end to end: differences only at rounding boundaries
+    assert_codes_differ_only_at_boundaries(a_c[rows], a_s[rows], c_own, s_own, y_own, xf)
 
     print(f"[full] {name}: oracle on sampled rows and columns", flush=True)
     b_c, b_s, _, _ = untile_np(bct.cpu().numpy(), bst.cpu().numpy(), N, K)
-    yh = y.float().cpu().numpy()
-    tol = 1e-5 if out_dtype == 0 else 2.0 ** -8      # bf16 output: one rounding of the fp32 result
-    assert rel_fro(yh[rows], linear.mxfp4_gemm(a_c[rows], a_s[rows], b_c, b_s)) <= tol
-    assert rel_fro(yh[:, cols], linear.mxfp4_gemm(a_c, a_s, b_c[cols], b_s[cols])) <= tol
+    ri, ci = torch.from_numpy(rows).to(y32.device), torch.from_numpy(cols).to(y32.device)
+    y_rows, y_cols = y32[ri].cpu().numpy(), y32[:, ci].cpu().numpy()
+    ref_rows = linear.mxfp4_gemm(a_c[rows], a_s[rows], b_c, b_s)
+    ref_cols = linear.mxfp4_gemm(a_c, a_s, b_c[cols], b_s[cols])
+    assert rel_fro(y_rows, ref_rows) <= 1e-5
+    assert rel_fro(y_cols, ref_cols) <= 1e-5
+    assert np.all(np.abs(y_rows - ref_rows) <= ELEM_TOL * per_element_gemm_bound(a_c[rows], a_s[rows], b_c, b_s, mxfp4.dequantize))
+    assert np.all(np.abs(y_cols - ref_cols) <= ELEM_TOL * per_element_gemm_bound(a_c, a_s, b_c[cols], b_s[cols], mxfp4.dequantize))
+    if out_dtype != 0:
+        np.testing.assert_array_equal(bf16_dev_to_bits(y[ri]), linear.round_to_bf16_bits(y_rows))
+        np.testing.assert_array_equal(bf16_dev_to_bits(y[:, ci].contiguous()), linear.round_to_bf16_bits(y_cols))
+        # the whole result, on the device: every bf16 entry is the round-to-nearest-even of the fp32 entry
+        u = y32.view(torch.int32)
+        rne = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).to(torch.int16)
+        assert torch.equal(rne, y.view(torch.int16))
 
 
 def test_70b_down_proj_full_size():

@@ -6,7 +6,7 @@ import pytest
 
 import workloads as wl
 from oracle import mxfp4, pipeline, rotation
-from helpers import rotation_error_ratio, to_dev, to_dev_bf16
+from helpers import assert_codes_differ_only_at_boundaries, rotation_error_ratio, to_dev, to_dev_bf16
 
 pytestmark = pytest.mark.gpu
 ROT_TOL = 1e-5
@@ -117,24 +117,24 @@ def test_strided_input_rows(env):
     assert torch.equal(codes, c_ref) and torch.equal(scales, s_ref)
 
 
-def test_end_to_end_codes_differ_only_at_rounding_boundaries(env):
-    """Device rotation vs oracle rotation, each quantised by its own side: not graded bit-exact (the
-    fp32 sums differ in the last bits); every differing code must be an adjacent-code flip."""
+@pytest.mark.parametrize("T,K,spec", [
+    (128, 4096, (wl.OutlierSpec(8, 50.0),)),
+    (2048, 4096, (wl.OutlierSpec(8, 50.0), wl.OutlierSpec(4, 1000.0, 8))),
+])
+def test_end_to_end_codes_differ_only_at_rounding_boundaries(env, T, K, spec):
+    """Device rotation vs oracle rotation, each quantised by its own side: not bit-exact by construction (the fp32
+    sums differ in the last bits), but at most 1e-5 of the codes and scales may differ, and each difference must sit
+    where the rotation tolerance allows one: the oracle's value within 1e-5 * ||x_block||_2 of a rounding boundary
+    of Eq. 2, or its group maximum that close to a power of two."""
     torch, duqpp = env
-    T, K = 128, 4096
-    xb = wl.make_activations("gpu-rq-e2e", T, K, (wl.OutlierSpec(8, 50.0),))
-    R = wl.make_rotation_blocks("gpu-rq-e2e", K // 32)
+    xb = wl.make_activations(f"gpu-rq-e2e-{T}", T, K, spec)
+    R = wl.make_rotation_blocks(f"gpu-rq-e2e-{T}", K // 32)
     codes, scales = duqpp.rotate_quantize(to_dev_bf16(xb, torch), to_dev(R, torch))
     torch.cuda.synchronize()
-    c_ref, s_ref, _ = pipeline.rotate_quantize(xb, R)
-    u, u_ref = mxfp4.unpack_codes(codes.cpu().numpy()), mxfp4.unpack_codes(c_ref)
-    same_scale = np.repeat(scales.cpu().numpy() == s_ref, 32, axis=1)
-    diff = (u != u_ref) & same_scale
-    frac = diff.mean()
-    print(f"[rotq] end-to-end differing codes: {frac:.2e}; differing scales: {(~same_scale).mean():.2e}", flush=True)
-    assert frac < 1e-3 and (~same_scale).mean() < 1e-3
-    d = np.abs((u[diff] & 7).astype(int) - (u_ref[diff] & 7).astype(int))
-    assert np.all(d <= 1)
+    c_ref, s_ref, y_ref = pipeline.rotate_quantize(xb, R)
+    n_c, n_s = assert_codes_differ_only_at_boundaries(codes.cpu().numpy(), scales.cpu().numpy(), c_ref, s_ref, y_ref,
+                                                      wl.bf16_bits_to_f32(xb))
+    print(f"[rotq] end-to-end T={T}: {n_c} of {T * K} codes and {n_s} of {T * K // 32} scales differ", flush=True)
 
 
 def test_quantize_weights(env):

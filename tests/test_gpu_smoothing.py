@@ -6,7 +6,8 @@ import pytest
 
 import workloads as wl
 from oracle import linear, mxfp4, pipeline, rotation, smoothing
-from helpers import rel_fro, rotation_error_ratio, to_dev, to_dev_bf16, untile_np
+from helpers import (assert_codes_differ_only_at_boundaries, rel_fro, rotation_error_ratio, to_dev, to_dev_bf16,
+                     untile_np)
 
 pytestmark = pytest.mark.gpu
 
@@ -59,8 +60,8 @@ def test_smoothed_path_against_the_definition(env, T, N, K):
     np.testing.assert_array_equal(ac.cpu().numpy(), c_ref)
     np.testing.assert_array_equal(asc.cpu().numpy(), s_ref)
     # end to end (each side in its own precision): codes differ only at rounding boundaries
-    c_def, s_def, _ = pipeline.rotate_quantize(xb, R, lam=lam)
-    assert np.mean(ac.cpu().numpy() != c_def) < 1e-3
+    c_def, s_def, y_def = pipeline.rotate_quantize(xb, R, lam=lam)
+    assert_codes_differ_only_at_boundaries(ac.cpu().numpy(), asc.cpu().numpy(), c_def, s_def, y_def, xs)
 
     # weights, tiled, and the product
     bct, bst = duqpp.quantize_weights_tiled(w, Rw)
@@ -70,8 +71,9 @@ def test_smoothed_path_against_the_definition(env, T, N, K):
     a_c, a_s, _, _ = untile_np(act.cpu().numpy(), ast.cpu().numpy(), T, K)
     np.testing.assert_array_equal(a_c, ac.cpu().numpy())
     b_c, b_s, _, _ = untile_np(bct.cpu().numpy(), bst.cpu().numpy(), N, K)
-    cw_def, sw_def, _ = pipeline.quantize_weights(wb, R, lam=lam)
-    assert np.mean(b_c != cw_def) < 1e-3
+    cw_def, sw_def, yw_def = pipeline.quantize_weights(wb, R, lam=lam)
+    assert_codes_differ_only_at_boundaries(b_c, b_s, cw_def, sw_def, yw_def,
+                                           wf.astype(np.float64) * lam.astype(np.float64)[None, :])
     assert rel_fro(y.cpu().numpy(), linear.mxfp4_gemm(a_c, a_s, b_c, b_s)) <= 1e-5
     # ungraded sanity: smoothing + rotation + W4A4 still approximates X W^T
     exact = xf.astype(np.float64) @ wf.astype(np.float64).T
