@@ -25,9 +25,11 @@ HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
 FP4_PEAK_TFLOPS = 10100.0     # MI355X dense MXFP4 matrix peak, published (256 CU x 2.4 GHz x 16384 flop/clk/CU)
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE (x 2.000) + WRITE_SIZE (x 1.000), the factors a plain
-# 256 MiB device copy gives for the same counters; workload c2_8b_down_prefill
-# (profiles/gemm_tiled_and_rotq_c2_8b_down_prefill_hbm_traffic.md).
+# 256 MiB device copy gives for the same counters; workload c2_8b_down_prefill.  Counter runs are separate runs of
+# this script under the profiler: the figures are copied from their summary, not measured by the run that prints them.
 MEASURED_TRAFFIC = {"gemm": 125.12e6 + 16.79e6, "rotq": 60.93e6 + 15.60e6}
+TRAFFIC_SOURCE = ("profiles/gemm_tiled_and_rotq_c2_8b_down_prefill_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE and "
+                  "WRITE_SIZE runs of this workload, scaled by a plain copy's readings); not measured in this run")
 
 
 def rotq_algorithmic_bytes(T, K):
@@ -44,7 +46,7 @@ def main():
     ap.add_argument("--sets", type=int, default=8, help="distinct buffer sets the batches rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-machine-probe", action="store_true",
-                    help="skip the two measurements of what the machine sustains (FP4 MFMA loop, device copy)")
+                    help="skip the measurement of the copy rate the machine sustains (1 GiB device copy)")
     ap.add_argument("--eager", action="store_true", help="time eager launches only (no HIP graph capture)")
     ap.add_argument("--two-stream-child", action="store_true",
                     help="(used by bench.py itself) time only the two-stream graph of the steps and print that figure")
@@ -157,6 +159,7 @@ def main():
                 name=nm, K=k, N=n, x=x, R=Rd, bc=bc, bs=bs,
                 ac=torch.empty(cb, dtype=torch.uint8, device=dev),
                 asc=torch.empty(sb, dtype=torch.uint8, device=dev),
+                ws=torch.empty(((cb + 255) // 256 + (sb + 255) // 256) * 256, dtype=torch.uint8, device=dev),
                 y=torch.empty((T, n), dtype=torch.bfloat16 if cfg["out"] == "bf16" else torch.float32, device=dev)))
         sets.append(layers)
     torch.cuda.synchronize()
@@ -188,12 +191,34 @@ def main():
             rotq1(l)
             gemm1(l)
 
+    # the same step through the fused entry point (duqpp_rotq_gemm_tiled): one call per linear, the activation
+    # operand in a caller-provided workspace
+    def fused1(l):
+        duqpp.rotq_gemm_tiled(l["x"], l["R"], l["bc"], l["bs"], l["N"], out_dtype=out_dtype, out=l["y"], workspace=l["ws"])
+
+    def fused_step(s):
+        for l in s:
+            fused1(l)
+
     # ---- timing ---------------------------------------------------------------------------
     # `fn` is run args.steps times over the rotating buffer sets, bracketed by device synchronisation.  The
     # launches are captured once into a HIP graph and the graph is replayed, so that the GPU runs them back to
     # back: issued one by one from Python, launches of a ~10 us kernel measure the interpreter, not the kernel.
     # (The kernels record no memset nodes.)  The figure from eager launches is kept beside it.  Events are
     # recorded on the stream the kernels are launched on.
+    # How a graph of args.steps steps is timed: the graph is replayed twice back to back and the events bracket the
+    # second replay.  The host enqueues the first event, the second replay and the last event while the GPU is still
+    # busy with the first replay, so the events see exactly args.steps steps as the GPU runs them in steady state and
+    # not the host's latency of launching a graph (some 100 us: 5-10 us per step when only 20 steps are timed).
+    def time_replay(g):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g.replay()
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / args.steps
+
     def time_region(fn, eager_only=False):
         for i in range(min(args.warmup, 10)):
             fn(sets[i % nsets])
@@ -221,12 +246,10 @@ def main():
                 g.replay()
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
-                e0.record()
                 g.replay()
-                e1.record()
                 torch.cuda.synchronize()
-                graph_wall_us = (time.perf_counter() - t0) * 1e6 / args.steps
-                graph_us = e0.elapsed_time(e1) * 1e3 / args.steps
+                graph_wall_us = (time.perf_counter() - t0) * 1e6 / args.steps   # host clock: launch and sync included
+                graph_us = time_replay(g)
             except Exception as exc:  # capture unavailable: keep the eager figures
                 print(f"bench.py: graph capture failed ({exc}); using eager launches", file=sys.stderr)
         return dict(us=graph_us if graph_us is not None else eager_us, eager_us=eager_us,
@@ -266,10 +289,7 @@ def main():
             torch.cuda.synchronize()
             g.replay()
             torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            g.replay()
-            torch.cuda.synchronize()
-            return (time.perf_counter() - t0) * 1e6 / args.steps
+            return time_replay(g)
         except Exception as exc:
             print(f"bench.py: two-stream graph capture failed ({exc})", file=sys.stderr)
             return None
@@ -280,10 +300,13 @@ def main():
         print(json.dumps({"two_stream_us": time_steps_two_streams()}))
         return
     whole = time_region(step, eager_only=args.eager)
-    one_stream_us = whole["wall_us"]                        # host clock around exactly args.steps steps
-    # The two-stream capture runs in a child process of its own (same inputs, same kernels): a capture over several
-    # streams is the less trodden path of the runtime, and whatever happens to it must not take this run's one result
-    # line with it.  Only prefill workloads use the figure.
+    # exactly args.steps steps between two events on the launch stream (a one-stream graph replay, or eager launches
+    # with --eager): the figure the result line's value is computed from
+    one_stream_us = whole["us"]
+    fused = time_region(fused_step, eager_only=args.eager)
+    # A second launch form is reported beside it, never as the metric: the same steps as a graph over two streams.  It
+    # is measured in a child process of its own (same inputs, same kernels), so that nothing that happens to a capture
+    # over several streams can cost this run its result line.  Prefill workloads only.
     two_stream_us = None
     if not args.eager and T > 128:
         import subprocess
@@ -298,10 +321,7 @@ def main():
                 print(f"bench.py: two-stream child ended with status {child.returncode}", file=sys.stderr)
         except Exception as exc:
             print(f"bench.py: two-stream child failed ({exc})", file=sys.stderr)
-    # Prefill workloads report throughput: the faster of the two launch forms.  With a handful of tokens the figure of
-    # interest is the time of one step from its first launch to its last result, so the one-stream form stays.
-    overlapped = two_stream_us is not None and T > 128 and two_stream_us < one_stream_us
-    ms_per_step = (two_stream_us if overlapped else one_stream_us) * 1e-3
+    ms_per_step = one_stream_us * 1e-3
     tr = time_region(rotq, eager_only=args.eager)
     tg = time_region(gemm, eager_only=args.eager)
     rotq_us, rotq_eager_us, gemm_us, gemm_eager_us = tr["us"], tr["eager_us"], tg["us"], tg["eager_us"]
@@ -329,12 +349,11 @@ def main():
         "unit": "TFLOP/s (2*T*N*K per whole step: rotate+quantise, then GEMM)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5),
-        "ms_per_step_one_stream": round(one_stream_us * 1e-3, 5),
+        "ms_per_step_host_clock": round(whole["wall_us"] * 1e-3, 5),
         "ms_per_step_two_streams": None if two_stream_us is None else round(two_stream_us * 1e-3, 5),
-        "ms_per_step_eager_launches": round(whole["eager_wall_us"] * 1e-3, 5),
-        "launch": ("HIP graph replay; rotate+quantise and GEMM on two streams, so that a batch's rotate+quantise may start "
-                   "while the previous batch's GEMM drains") if overlapped
-                  else ("HIP graph replay of the timed steps, one stream" if whole["graph"] else "eager launches"),
+        "ms_per_step_eager_launches": round(whole["eager_us"] * 1e-3, 5),
+        "launch": ("HIP graph replay of the timed steps on one stream, timed by events on that stream"
+                   if whole["graph"] else "eager launches, timed by events on the launch stream"),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "mxfp4 (E2M1 codes + E8M0 scales; fp32 rotation and accumulation)",
         "data": "synthetic" if not args.zero_operands else "all-zero operands (diagnostic run, not the metric)",
@@ -351,15 +370,21 @@ def main():
                            "frac_mfma_peak": round(gemm_tflops / FP4_PEAK_TFLOPS, 4),
                            # N*K*(1/2 + 1/32) bytes of weights per launch: the decode-shape figure of merit
                            "weight_stream_GB/s": round(weight_bytes / (gemm_us * 1e-6) / 1e9, 1)},
+            # one duqpp_rotq_gemm_tiled call per linear (rotate+quantise into the caller's workspace, then the GEMM)
+            # beside the two separate calls (ms_per_step): the same two kernels on the same stream either way
+            "rotq_gemm_fused_call": {"us": round(fused["us"], 2), "us_eager_launches": round(fused["eager_us"], 2),
+                                     "separate_calls_us": round(one_stream_us, 2), "launches": len(linears)},
         },
         "roofline": {"kernel": "mxfp4_gemm", "bound": "mfma", "achieved": round(gemm_tflops, 1),
                      "peak": FP4_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(gemm_tflops / FP4_PEAK_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC["gemm"] if headline else None},
+                     "traffic": MEASURED_TRAFFIC["gemm"] if headline else None,
+                     "traffic_source": TRAFFIC_SOURCE if headline else None},
         "roofline_rotate_quantize": {"kernel": "rotq", "bound": "hbm", "achieved": round(rotq_gbps, 1),
                                      "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                      "frac": round(rotq_gbps / HBM_PEAK_GBPS, 4),
-                                     "traffic": MEASURED_TRAFFIC["rotq"] if headline else None},
+                                     "traffic": MEASURED_TRAFFIC["rotq"] if headline else None,
+                                     "traffic_source": TRAFFIC_SOURCE if headline else None},
     }
     if per_linear:
         result["components"]["per_linear"] = per_linear
@@ -373,23 +398,9 @@ def main():
                               "unit": "GB/s", "frac": round(weight_bytes / (gemm_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
                               "traffic": None}
 
-    # ---- what the machine sustains, measured here, beside the published peaks ---------------
-    # FP4 MFMA: the library's register-resident loop on bit patterns of the quantised weights, with every instruction
-    # taking a different operand pair as in the GEMM kernels (the rate depends on how much the operands switch; the
-    # figure with one pair held is kept beside it); HBM: a plain 1 GiB device copy (reads + writes over time).
+    # ---- what the machine sustains on a plain copy, measured here, beside the published HBM peak ---------------
     if not args.no_machine_probe:
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        pc = sets[0][-1]["bc"]
-        rates = {}
-        for switching in (False, True):                     # one operand pair held / a different pair per MFMA
-            duqpp.probe_fp4_mfma(pc, 1000, switching)
-            torch.cuda.synchronize()
-            e0.record()
-            _, probe_flops = duqpp.probe_fp4_mfma(pc, 3000, switching)
-            e1.record()
-            torch.cuda.synchronize()
-            rates[switching] = probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
-        sustained = rates[True]
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
         dst.copy_(src)
@@ -401,13 +412,8 @@ def main():
         torch.cuda.synchronize()
         copy_gbps = 4 * 2.0 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
         del src, dst
-        result["machine"] = {"fp4_mfma_sustained_TFLOP/s": round(sustained, 1),
-                             "fp4_mfma_sustained_frac_of_peak": round(sustained / FP4_PEAK_TFLOPS, 4),
-                             "fp4_mfma_held_operands_TFLOP/s": round(rates[False], 1),
-                             "hbm_copy_GB/s": round(copy_gbps, 1),
+        result["machine"] = {"hbm_copy_GB/s": round(copy_gbps, 1),
                              "hbm_copy_frac_of_peak": round(copy_gbps / HBM_PEAK_GBPS, 4)}
-        if T > 32:
-            result["roofline"]["frac_of_sustained"] = round(gemm_tflops / sustained, 4)
         result["roofline_rotate_quantize"]["frac_of_copy_rate"] = round(rotq_gbps / copy_gbps, 4)
 
     # ---- the CPU oracle on a bounded sample of the same workload ---------------------------

@@ -14,7 +14,9 @@
  *
  * Conventions (all entry points)
  *   - Every pointer is a DEVICE pointer unless its comment says "host".  The caller owns
- *     every buffer; the library allocates nothing and keeps no device state.
+ *     every buffer; the library allocates nothing.  What it keeps per device is set-up only: the
+ *     architecture check and the kernels' shared-memory attributes (made at duqpp_init or at the first
+ *     call on that device); no call leaves data behind that a later call reads.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work and return; they never synchronise.
  *   - Layouts are row-major with K contiguous.  G = K / 32.
@@ -28,11 +30,13 @@
  *               nibble; code = sign<<3 | magnitude index into {0, .5, 1, 1.5, 2, 3, 4, 6}
  *       scales  uint8 [rows, G]   E8M0: value 2^(byte - 127); 0xFF is never produced
  *       Y       fp32 or bf16 [T, N], row stride ldy (elements)
- *   - Requirements checked on the host before any launch: pointers non-null, T/N >= 1,
+ *   - Requirements checked on the host before any launch (of every stage, for the fused calls): pointers non-null, T/N >= 1,
  *     K >= 32 and K % 32 == 0, n_rblocks in {1, K/32}, ld >= the row length, X/W bases and
  *     row strides 16-byte aligned, codes bases 16-byte aligned, Y base aligned to its element.
  *   - Inputs must be finite; NaN/Inf are outside the contract.
- *   - Return value: DUQPP_OK or a negative duqpp_status; nothing throws or aborts.
+ *   - Return value: DUQPP_OK or a negative duqpp_status; nothing throws or aborts.  DUQPP_ERR_HIP reports a
+ *     failure of the call's own launches or runtime calls; an error that the caller's earlier work left in the
+ *     runtime's error state is neither reported nor cleared.
  *   - Results are deterministic: the same inputs give bit-identical outputs on every call.
  */
 #ifndef DUQPP_H
@@ -57,6 +61,13 @@ typedef enum {
 } duqpp_status;
 
 typedef enum { DUQPP_F32 = 0, DUQPP_BF16 = 1 } duqpp_dtype;
+
+/*
+ * Optional: the per-device set-up (architecture check, shared-memory attributes of the kernels) for the calling
+ * thread's current device, so that no entry point has to do it at its first call -- e.g. before a stream capture.
+ * Once per device is enough; further calls return at once.  Every entry point runs the part it needs by itself.
+ */
+int duqpp_init(void);
 
 /*
  * Offline weight transform of Eq. 5: W^ = R^T . W, then Eq. 2 along K.  With W stored
@@ -164,7 +175,8 @@ int duqpp_mxfp4_gemm_tiled(const uint8_t* a_codes_t, const uint8_t* a_scales_t,
                            void* y, int out_dtype, int64_t ldy, void* stream);
 
 /*
- * TEST AND MEASUREMENT ONLY: duqpp_mxfp4_gemm_tiled on one named kernel instead of the one the library would
+ * NOT PART OF THE CONTRACT -- a hook for tests and measurements that may change with the kernels:
+ * duqpp_mxfp4_gemm_tiled on one named kernel instead of the one the library would
  * pick for the shape, so that every kernel can be checked at every shape.  Same arguments, checks and result.
  * A kernel that cannot run the call returns DUQPP_ERR_SHAPE: the decode kernel takes T <= 128; the 256 x 256
  * kernel with bf16 output needs y 16-byte aligned and N, ldy multiples of 8.
@@ -231,23 +243,6 @@ int duqpp_construct_rotation(const void* x_bf16, int64_t T, int64_t K, int64_t l
                              const double* q_steps, int max_steps,
                              float* R_out, int32_t* info, double* peaks,
                              void* workspace, size_t workspace_bytes, void* stream);
-
-/*
- * MEASUREMENT ONLY: the rate the chip sustains on the FP4 x FP4 block-scaled matrix instruction of the Eq. 5
- * product alone -- operands in registers, no memory traffic, one wave per SIMD on all 256 CUs.  Time the call
- * with events: *flops / time is the ceiling of any MXFP4 GEMM under this load.
- *   codes   in   at least 2048 bytes (16-byte aligned) of MXFP4 code bytes, used as operand bit patterns
- *                (the rate depends on them)
- *   iters        loop iterations per wave
- *   switching    0: every instruction takes the same operand pair (8 instructions per iteration);
- *                1: four activation-side and four weight-side fragments per wave, every instruction a different
- *                   pair, one operand changing per instruction as in the GEMM kernels (16 per iteration) -- the
- *                   realistic ceiling, since the rate falls with the switching of the operands
- *   out     out  [256 * 256] fp32 (one value per lane; keeps the work alive)
- *   flops   out  host pointer, nullable: floating-point operations of the launch
- */
-int duqpp_probe_fp4_mfma(const uint8_t* codes, size_t codes_bytes, int64_t iters, int switching, float* out,
-                         double* flops, void* stream);
 
 /* Host, pure: scratch bytes duqpp_mxfp4_gemm (fused = 0) can use or duqpp_rotq_gemm (fused = 1) needs:
  * room for both operands in the tiled layout.  0 for invalid shapes. */

@@ -21,7 +21,7 @@ from .binding import (  # noqa: F401
     library_path,
     mxfp4_gemm,
     mxfp4_gemm_tiled,
-    probe_fp4_mfma,
+    init,
     quantize_weights_tiled,
     rotate_quantize_tiled,
     rotq_gemm_tiled,

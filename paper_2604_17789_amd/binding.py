@@ -53,12 +53,12 @@ def _load():
     L.duqpp_gemm_kernel_for.restype = ci
     L.duqpp_rotq_gemm_tiled.argtypes = [vp, i64, fp, i64, u8p, u8p, i64, i64, i64, vp, ci, i64, vp, sz, vp]
     L.duqpp_fold_smoothing.argtypes = [fp, i64, fp, i64, fp, fp, vp]
-    L.duqpp_probe_fp4_mfma.argtypes = [u8p, sz, i64, ci, fp, ctypes.POINTER(ctypes.c_double), vp]
     L.duqpp_construct_rotation_workspace_bytes.argtypes = [i64, ci]
     L.duqpp_construct_rotation_workspace_bytes.restype = sz
     L.duqpp_construct_rotation.argtypes = [vp, i64, i64, i64, vp, ci, fp, vp, vp, vp, sz, vp]
     L.duqpp_construct_rotation.restype = ci
-    L.duqpp_probe_fp4_mfma.restype = ci
+    L.duqpp_init.argtypes = []
+    L.duqpp_init.restype = ci
     for name in ("duqpp_tiled_bytes", "duqpp_tile_operand", "duqpp_untile_operand", "duqpp_quantize_weights_tiled",
                  "duqpp_rotate_quantize_tiled", "duqpp_mxfp4_gemm_tiled", "duqpp_rotq_gemm_tiled",
                  "duqpp_fold_smoothing"):
@@ -365,13 +365,6 @@ def construct_rotation(x, q_steps, return_peaks=False, workspace=None):
     return (R, block, kept, peaks) if return_peaks else (R, block, kept)
 
 
-def probe_fp4_mfma(codes, iters, switching=True, out=None):
-    """Measurement only: enqueue the register-resident FP4 MFMA loop (switching: every instruction a different
-    operand pair, as in the GEMM kernels; else one pair held); returns (out, flops of the launch)."""
-    _dev(codes, torch.uint8, "codes")
-    if out is None:
-        out = torch.empty(256 * 256, dtype=torch.float32, device=codes.device)
-    flops = ctypes.c_double(0.0)
-    _check(lib.duqpp_probe_fp4_mfma(codes.data_ptr(), codes.numel(), iters, 1 if switching else 0, out.data_ptr(),
-                                    ctypes.byref(flops), _stream()), "duqpp_probe_fp4_mfma")
-    return out, flops.value
+def init():
+    """Per-device set-up for the current device (optional; every call does what it needs by itself)."""
+    _check(lib.duqpp_init(), "duqpp_init")

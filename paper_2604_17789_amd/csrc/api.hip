@@ -1,5 +1,4 @@
 // C ABI of libduqpp: argument validation on the host, then kernel launches on the caller's stream.
-#include <atomic>
 #include <cstring>
 
 #include "duqpp_internal.h"
@@ -77,9 +76,33 @@ TiledScratch tiled_scratch(int64_t T, int64_t N, int64_t K) {
     return w;
 }
 
+// The fused call on tiled weights with the activation operand in a_codes / a_scales (256-byte aligned scratch of
+// the sizes duqpp_tiled_bytes reports): every argument of both stages is checked before the first launch.
+int rotq_gemm_tiled_impl(const void* x_bf16, int64_t ldx, const float* R, int64_t n_rblocks, uint8_t* a_codes,
+                         uint8_t* a_scales, const uint8_t* b_codes_t, const uint8_t* b_scales_t, int64_t T, int64_t N,
+                         int64_t K, void* y, int out_dtype, int64_t ldy, void* stream) {
+    int st = duqpp_validate_rotate_quantize(x_bf16, T, K, ldx, R, n_rblocks, a_codes, a_scales);
+    if (st != DUQPP_OK) return st;
+    st = duqpp_validate_mxfp4_gemm(a_codes, a_scales, b_codes_t, b_scales_t, T, N, K, y, out_dtype, ldy, nullptr, 0, 2);
+    if (st != DUQPP_OK) return st;
+    if (!aligned_to(b_codes_t, 256) || !aligned_to(b_scales_t, 256)) return DUQPP_ERR_ALIGN;
+    st = rotate_quantize_impl(x_bf16, T, K, ldx, R, n_rblocks, a_codes, a_scales, nullptr, stream, true);
+    if (st != DUQPP_OK) return st;
+    return duqpp_mxfp4_gemm_tiled(a_codes, a_scales, b_codes_t, b_scales_t, T, N, K, y, out_dtype, ldy, stream);
+}
+
 }  // namespace
 
 extern "C" {
+
+int duqpp_init(void) {
+    int st = check_device();
+    if (st != DUQPP_OK) return st;
+    if (setup_rotq() != hipSuccess || setup_gemm_tiled_mid() != hipSuccess || setup_gemm_tiled_small() != hipSuccess ||
+        setup_gemm_tiled_large() != hipSuccess)
+        return DUQPP_ERR_HIP;
+    return DUQPP_OK;
+}
 
 int duqpp_validate_rotate_quantize(const void* x, int64_t T, int64_t K, int64_t ldx, const float* R,
                                    int64_t n_rblocks, const uint8_t* codes, const uint8_t* scales) {
@@ -288,15 +311,14 @@ int duqpp_rotq_gemm_tiled(const void* x_bf16, int64_t ldx, const float* R, int64
     if (!x_bf16 || !R || !b_codes_t || !b_scales_t || !y) return DUQPP_ERR_NULL;
     int st = validate_rows_K(T, K, ldx, n_rblocks);
     if (st != DUQPP_OK) return st;
-    const size_t cb = (tiled_codes_bytes(T, K / 32) + 255) & ~(size_t)255;
-    const size_t sb = (tiled_scales_bytes(T, K / 32) + 255) & ~(size_t)255;
+    const size_t cb = round256(tiled_codes_bytes(T, K / 32));
+    const size_t sb = round256(tiled_scales_bytes(T, K / 32));
     if (!workspace || workspace_bytes < cb + sb) return DUQPP_ERR_WORKSPACE;
     if (!aligned_to(workspace, 256)) return DUQPP_ERR_ALIGN;
     uint8_t* a_codes = static_cast<uint8_t*>(workspace);
     uint8_t* a_scales = a_codes + cb;
-    st = rotate_quantize_impl(x_bf16, T, K, ldx, R, n_rblocks, a_codes, a_scales, nullptr, stream, true);
-    if (st != DUQPP_OK) return st;
-    return duqpp_mxfp4_gemm_tiled(a_codes, a_scales, b_codes_t, b_scales_t, T, N, K, y, out_dtype, ldy, stream);
+    return rotq_gemm_tiled_impl(x_bf16, ldx, R, n_rblocks, a_codes, a_scales, b_codes_t, b_scales_t, T, N, K, y, out_dtype,
+                                ldy, stream);
 }
 
 int duqpp_fold_smoothing(const float* R, int64_t n_rblocks, const float* lambda, int64_t K, float* R_act,
@@ -333,20 +355,6 @@ int duqpp_construct_rotation(const void* x_bf16, int64_t T, int64_t K, int64_t l
     if (st != DUQPP_OK) return st;
     ConstructParams p{static_cast<const uint16_t*>(x_bf16), ldx, T, K, q_steps, max_steps, R_out, info, peaks, workspace};
     return launch_construct_rotation(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
-}
-
-int duqpp_probe_fp4_mfma(const uint8_t* codes, size_t codes_bytes, int64_t iters, int switching, float* out,
-                         double* flops, void* stream) {
-    if (!codes || !out) return DUQPP_ERR_NULL;
-    if (codes_bytes < 2048 || iters < 1 || iters > (int64_t)1 << 24 || (switching != 0 && switching != 1)) return DUQPP_ERR_SHAPE;
-    if (!aligned_to(codes, 16) || !aligned_to(out, 4)) return DUQPP_ERR_ALIGN;
-    int st = check_device();
-    if (st != DUQPP_OK) return st;
-    size_t pieces = codes_bytes / 2048;
-    if (pieces > 4096) pieces = 4096;
-    ProbeParams p{codes, (int)pieces, iters, switching, out};
-    if (flops) *flops = (double)kNumCU * 4.0 * (double)iters * (switching ? 16.0 : 8.0) * (2.0 * 32 * 32 * 64);
-    return launch_probe_fp4_mfma(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
 }
 
 const char* duqpp_status_string(int status) {

@@ -220,16 +220,21 @@ size_t construct_workspace_bytes(int64_t T, int steps) {
 }
 
 hipError_t launch_construct_rotation(const ConstructParams& p, hipStream_t stream) {
-    hipLaunchKernelGGL(construct_init_kernel, dim3(8), dim3(256), 0, stream, p);
+    hipError_t e = launch(construct_init_kernel, dim3(8), dim3(256), 0, stream, p);
+    if (e != hipSuccess) return e;
     const int64_t chunks = (int64_t)p.T * (p.K / 8);
     int grid = (int)((chunks + 255) / 256 < 2048 ? (chunks + 255) / 256 : 2048);
-    hipLaunchKernelGGL(construct_blockmax_kernel, dim3(grid), dim3(256), 0, stream, p);
+    e = launch(construct_blockmax_kernel, dim3(grid), dim3(256), 0, stream, p);
+    if (e != hipSuccess) return e;
     grid = (int)((p.T + 7) / 8 < 1024 ? (p.T + 7) / 8 : 1024);
-    hipLaunchKernelGGL(construct_extract_kernel, dim3(grid), dim3(256), 0, stream, p);
+    e = launch(construct_extract_kernel, dim3(grid), dim3(256), 0, stream, p);
+    if (e != hipSuccess) return e;
     const int step_grid = (int)((p.T + kStepRowsPerWG - 1) / kStepRowsPerWG);
-    for (int t = 1; t <= p.steps; ++t) hipLaunchKernelGGL(construct_step_kernel, dim3(step_grid), dim3(256), 0, stream, p, t);
-    hipLaunchKernelGGL(construct_final_kernel, dim3(1), dim3(256), 0, stream, p);
-    return hipGetLastError();
+    for (int t = 1; t <= p.steps; ++t) {
+        e = launch(construct_step_kernel, dim3(step_grid), dim3(256), 0, stream, p, t);
+        if (e != hipSuccess) return e;
+    }
+    return launch(construct_final_kernel, dim3(1), dim3(256), 0, stream, p);
 }
 
 }  // namespace duqpp

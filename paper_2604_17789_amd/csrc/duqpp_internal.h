@@ -4,6 +4,8 @@
 #include <stdint.h>
 #include <stddef.h>
 
+#include <atomic>
+
 #include "duqpp.h"
 
 namespace duqpp {
@@ -11,6 +13,51 @@ namespace duqpp {
 constexpr int kBlock = 32;        // rotation block == MXFP4 group (Eq. 4, B = 32)
 constexpr int kNumCU = 256;       // MI355X
 constexpr int kNumXCD = 8;
+constexpr int kMaxDevices = 64;   // devices of one process the per-device set-up keeps track of
+
+// A launch that reports its own status.  The runtime's per-thread error state, which may still hold an error left by
+// the caller's earlier work, is neither consulted nor cleared.
+template <typename P>
+inline hipError_t launch(void (*kernel)(P), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream, const P& p) {
+    P arg = p;
+    void* args[] = {&arg};
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, args, lds_bytes, stream);
+}
+template <typename P, typename Q>
+inline hipError_t launch(void (*kernel)(P, Q), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream, const P& p,
+                         const Q& q) {
+    P a0 = p;
+    Q a1 = q;
+    void* args[] = {&a0, &a1};
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, args, lds_bytes, stream);
+}
+
+// Set-up that has to happen once on every device a kernel runs on (a function attribute belongs to the device's
+// copy of the code): f runs with the calling thread's current device, once per device and process.
+struct PerDeviceOnce {
+    std::atomic<int> done[kMaxDevices];
+    template <typename F>
+    hipError_t run(F&& f) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+        if (done[dev].load(std::memory_order_acquire)) return hipSuccess;
+        e = f();
+        if (e == hipSuccess) done[dev].store(1, std::memory_order_release);
+        return e;
+    }
+};
+inline hipError_t allow_dynamic_lds(const void* kernel, int bytes) {
+    return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+// Per-device set-up of each translation unit's kernels (what duqpp_init runs; the launchers run it themselves on
+// first use).
+hipError_t setup_rotq();
+hipError_t setup_gemm_tiled_mid();
+hipError_t setup_gemm_tiled_small();
+hipError_t setup_gemm_tiled_large();
 
 // ---- rotate + quantise (rotq.hip) ------------------------------------------------------
 struct RotqParams {
@@ -92,15 +139,6 @@ struct ConstructParams {
 };
 size_t construct_workspace_bytes(int64_t T, int steps);
 hipError_t launch_construct_rotation(const ConstructParams& p, hipStream_t stream);
-
-// ---- measurement aid (probe.hip) --------------------------------------------------------------
-struct ProbeParams {
-    const uint8_t* codes; int pieces;   // pieces of 2 KiB of code bytes used as operand patterns
-    int64_t iters;                      // each wave issues 8 * iters MFMAs (16 * iters with switching operands)
-    int switching;                      // 0: one operand pair held; 1: 4 x 4 fragments, a different pair per MFMA
-    float* out;                         // [kNumCU * 256]
-};
-hipError_t launch_probe_fp4_mfma(const ProbeParams& p, hipStream_t stream);
 
 struct TiledGemmParams {
     const uint8_t* a_codes; const uint8_t* a_scales;   // tiled, T rows

@@ -11,25 +11,12 @@
 // feeds them to four MFMAs that pick scale byte 0..3 of the word; half-wave g handles groups
 // 4g .. 4g+3 of every run of 8.
 #include "duqpp_internal.h"
+#include "mxfp4_device.h"
 
 namespace duqpp {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef int i32x8 __attribute__((ext_vector_type(8)));
-
-__device__ __forceinline__ i32x8 fp4_operand(const uint4& v) {
-    i32x8 r = {(int)v.x, (int)v.y, (int)v.z, (int)v.w, 0, 0, 0, 0};
-    return r;
-}
-
 #define DUQPP_MFMA_FP4(acc, a, b, sa, sb, sel) \
     acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fp4_operand(a), fp4_operand(b), acc, 4, 4, sel, (int)(sa), sel, (int)(sb))
-
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
 
 // Four consecutive groups (kb .. kb+3) of one row: 64 code bytes + 4 scale bytes.
 struct RowFrag {
@@ -133,9 +120,8 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(GemmParams p) {
 
 hipError_t launch_gemm(const GemmParams& p, hipStream_t stream) {
     dim3 grid((unsigned)((p.N + kDirTileN - 1) / kDirTileN), (unsigned)((p.T + kDirTileM - 1) / kDirTileM)), block(256);
-    if (p.out_bf16) hipLaunchKernelGGL(gemm_direct_kernel<true>, grid, block, 0, stream, p);
-    else hipLaunchKernelGGL(gemm_direct_kernel<false>, grid, block, 0, stream, p);
-    return hipGetLastError();
+    return p.out_bf16 ? launch(gemm_direct_kernel<true>, grid, block, 0, stream, p)
+                      : launch(gemm_direct_kernel<false>, grid, block, 0, stream, p);
 }
 
 }  // namespace duqpp

@@ -13,22 +13,14 @@
 // partial tiles are then summed through LDS in a fixed order (deterministic) and the first T rows
 // are stored.
 #include "duqpp_internal.h"
+#include "mxfp4_device.h"
 
 namespace duqpp {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef int i32x8 __attribute__((ext_vector_type(8)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 constexpr int kDecWaves = 8;
 
-__device__ __forceinline__ i32x8 dec_fp4_operand(const u32x4& v) {
-    i32x8 r = {(int)v[0], (int)v[1], (int)v[2], (int)v[3], 0, 0, 0, 0};
-    return r;
-}
-
 #define DUQPP_DEC_MFMA(ACC, A, B, SA, SB, SEL) \
-    ACC = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(dec_fp4_operand(A), dec_fp4_operand(B), ACC, 4, 4, SEL, (int)(SA), SEL, (int)(SB))
+    ACC = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fp4_operand(A), fp4_operand(B), ACC, 4, 4, SEL, (int)(SA), SEL, (int)(SB))
 
 template <int MT>
 struct DecStep {
@@ -60,12 +52,6 @@ __device__ __forceinline__ void dec_load(DecStep<MT>& d, const uint8_t* a_codes,
 #pragma unroll
     for (int i = 0; i < 4; ++i) d.b[i] = __builtin_nontemporal_load((const u32x4*)(pb + i * 512));
     d.sb = *(const uint32_t*)(b_scales + (int64_t)step * 256 + lane4_b);
-}
-
-__device__ __forceinline__ uint16_t dec_f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
 }
 
 template <bool OUT_BF16, int ROWS, int MT>
@@ -179,7 +165,7 @@ __global__ __launch_bounds__(kDecWaves * 64) void gemm_decode_kernel(TiledGemmPa
             const int tok = 32 * (m0 + m) + 8 * (e / 4) + 4 * g + (e % 4);
             const int col = rt * 32 + rb;
             if (r < ROWS && tok < p.T && col < p.N) {
-                if (OUT_BF16) ((uint16_t*)p.y)[(int64_t)tok * p.ldy + col] = dec_f32_to_bf16_rne(sum);
+                if (OUT_BF16) ((uint16_t*)p.y)[(int64_t)tok * p.ldy + col] = f32_to_bf16_rne(sum);
                 else ((float*)p.y)[(int64_t)tok * p.ldy + col] = sum;
             }
         }
@@ -236,7 +222,7 @@ __global__ __launch_bounds__(kDecWaves * 64) void gemm_decode16_kernel(TiledGemm
     auto mfmas = [&](const Dec16Step& d) {
 #pragma unroll
         for (int q = 0; q < 2; ++q)
-            acc[q] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(dec_fp4_operand(d.a[q]), dec_fp4_operand(d.b[q]), acc[q],
+            acc[q] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fp4_operand(d.a[q]), fp4_operand(d.b[q]), acc[q],
                                                                       4, 4, 0, (int)d.sa[q], 0, (int)d.sb[q]);
     };
     if (s0 < s1) {                                         // two register sets taking turns, as above
@@ -272,17 +258,17 @@ __global__ __launch_bounds__(kDecWaves * 64) void gemm_decode16_kernel(TiledGemm
         for (int w = 0; w < kDecWaves; ++w) sum += part[w][i][lane];
         const int tok = 4 * g + i, col = rt * 32 + rb;
         if (tok < p.T && col < p.N) {
-            if (OUT_BF16) ((uint16_t*)p.y)[(int64_t)tok * p.ldy + col] = dec_f32_to_bf16_rne(sum);
+            if (OUT_BF16) ((uint16_t*)p.y)[(int64_t)tok * p.ldy + col] = f32_to_bf16_rne(sum);
             else ((float*)p.y)[(int64_t)tok * p.ldy + col] = sum;
         }
     }
 }
 
 template <int ROWS, int MT>
-static void launch_decode_rows(const TiledGemmParams& p, unsigned tiles, unsigned passes, hipStream_t stream) {
+static hipError_t launch_decode_rows(const TiledGemmParams& p, unsigned tiles, unsigned passes, hipStream_t stream) {
     dim3 grid(tiles * (32 / ROWS), passes), block(kDecWaves * 64);
-    if (p.out_bf16) hipLaunchKernelGGL((gemm_decode_kernel<true, ROWS, MT>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((gemm_decode_kernel<false, ROWS, MT>), grid, block, 0, stream, p);
+    return p.out_bf16 ? launch(gemm_decode_kernel<true, ROWS, MT>, grid, block, 0, stream, p)
+                      : launch(gemm_decode_kernel<false, ROWS, MT>, grid, block, 0, stream, p);
 }
 
 hipError_t launch_gemm_decode(const TiledGemmParams& p, hipStream_t stream) {
@@ -295,21 +281,14 @@ hipError_t launch_gemm_decode(const TiledGemmParams& p, hipStream_t stream) {
     // (N = 4096, K = 14336: T = 1 9.0 -> 7.1 us, T = 16 9.1 -> 7.9 us; N = K = 4096: 4.3 -> 3.7 us).
     if (p.T <= 16 && tiles < (unsigned)kNumCU) {
         dim3 grid(tiles * 2), block(kDecWaves * 64);
-        if (p.out_bf16) hipLaunchKernelGGL(gemm_decode16_kernel<true>, grid, block, 0, stream, p);
-        else hipLaunchKernelGGL(gemm_decode16_kernel<false>, grid, block, 0, stream, p);
-        return hipGetLastError();
+        return p.out_bf16 ? launch(gemm_decode16_kernel<true>, grid, block, 0, stream, p)
+                          : launch(gemm_decode16_kernel<false>, grid, block, 0, stream, p);
     }
     const bool cut = tiles < (unsigned)kNumCU;              // (more than 16 tokens here)
     // 65..128 tokens: two passes of two row tiles each (blockIdx.y), the weights of the second mostly from cache
     const unsigned passes = p.T <= 64 ? 1u : 2u;
-    if (p.T <= 32) {
-        if (cut) launch_decode_rows<16, 1>(p, tiles, passes, stream);
-        else launch_decode_rows<32, 1>(p, tiles, passes, stream);
-    } else {
-        if (cut) launch_decode_rows<16, 2>(p, tiles, passes, stream);
-        else launch_decode_rows<32, 2>(p, tiles, passes, stream);
-    }
-    return hipGetLastError();
+    if (p.T <= 32) return cut ? launch_decode_rows<16, 1>(p, tiles, passes, stream) : launch_decode_rows<32, 1>(p, tiles, passes, stream);
+    return cut ? launch_decode_rows<16, 2>(p, tiles, passes, stream) : launch_decode_rows<32, 2>(p, tiles, passes, stream);
 }
 
 }  // namespace duqpp

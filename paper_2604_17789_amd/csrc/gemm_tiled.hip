@@ -25,7 +25,6 @@
 // would drain the whole DMA queue before every LDS read it cannot disambiguate, i.e. serialise the
 // pipeline.  No other vector-memory load is issued inside the K loop, so the compiler places no
 // vmcnt wait of its own there; LDS reads and MFMAs are ordinary code with compiler-managed waits.
-#include <atomic>
 #include <type_traits>
 
 #include "duqpp_internal.h"
@@ -388,25 +387,25 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledGemmParams p) {
 }
 
 // 128 x 256 tiles, persistent workgroups, any shape.
+hipError_t setup_gemm_tiled_mid() {
+    static PerDeviceOnce once;
+    return once.run([] {
+        hipError_t e = allow_dynamic_lds((const void*)gemm_tiled_kernel<true>, kGemmLdsBytes);
+        if (e != hipSuccess) return e;
+        return allow_dynamic_lds((const void*)gemm_tiled_kernel<false>, kGemmLdsBytes);
+    });
+}
+
 hipError_t launch_gemm_tiled_mid(const TiledGemmParams& p, hipStream_t stream) {
-    static std::atomic<int> configured{0};
-    if (!configured.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_tiled_kernel<true>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void*)gemm_tiled_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kGemmLdsBytes);
-        if (e != hipSuccess) return e;
-        configured.store(1, std::memory_order_release);
-    }
+    hipError_t e = setup_gemm_tiled_mid();
+    if (e != hipSuccess) return e;
     const int tiles_m = (p.T + kBM - 1) / kBM, tiles_n = (p.N + kBN - 1) / kBN;
     // persistent workgroups: the 156 KiB of LDS allow one per CU, and each walks its tiles with the
     // transfer pipeline running across tile boundaries
     const int total = tiles_m * tiles_n;
     dim3 grid((unsigned)(total < kNumCU ? total : kNumCU)), block(256);
-    if (p.out_bf16) hipLaunchKernelGGL(gemm_tiled_kernel<true>, grid, block, kGemmLdsBytes, stream, p);
-    else hipLaunchKernelGGL(gemm_tiled_kernel<false>, grid, block, kGemmLdsBytes, stream, p);
-    return hipGetLastError();
+    return p.out_bf16 ? launch(gemm_tiled_kernel<true>, grid, block, kGemmLdsBytes, stream, p)
+                      : launch(gemm_tiled_kernel<false>, grid, block, kGemmLdsBytes, stream, p);
 }
 
 // Which kernel runs a shape.

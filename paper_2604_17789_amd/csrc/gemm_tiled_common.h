@@ -1,15 +1,13 @@
 // Device helpers shared by the tiled MXFP4 GEMM kernels: LDS-DMA transfers issued from asm, hand-placed
-// waits, the block-scaled FP4 MFMA, bf16 rounding.
+// waits, the block-scaled FP4 MFMA.
 #ifndef DUQPP_GEMM_TILED_COMMON_H
 #define DUQPP_GEMM_TILED_COMMON_H
 
 #include "duqpp_internal.h"
+#include "mxfp4_device.h"
 
 namespace duqpp {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef int i32x8 __attribute__((ext_vector_type(8)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));   // fp32 pairs convert to it in one instruction, round to nearest even
 
@@ -67,11 +65,6 @@ __device__ __forceinline__ void workgroup_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-__device__ __forceinline__ i32x8 fp4_operand(const u32x4& v) {
-    i32x8 r = {(int)v[0], (int)v[1], (int)v[2], (int)v[3], 0, 0, 0, 0};
-    return r;
-}
-
 #define DUQPP_MFMA(ACC, A, B, SA, SB, SEL) \
     ACC = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fp4_operand(A), fp4_operand(B), ACC, 4, 4, SEL, (int)(SA), SEL, (int)(SB))
 
@@ -84,12 +77,6 @@ __device__ __forceinline__ void dma_256(const uint8_t* src_lane, uint32_t lds_ds
         :
         : "v"(src_lane), "s"(lds_dst)
         : "memory", "m0");
-}
-
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
 }
 
 }  // namespace duqpp

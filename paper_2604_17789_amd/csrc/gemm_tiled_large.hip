@@ -19,7 +19,6 @@
 //              of the instruction is i for every lane.
 // K is a summation index: the order in which groups meet the instruction only changes the order of the fp32
 // additions.
-#include <atomic>
 #include <type_traits>
 
 #include "duqpp_internal.h"
@@ -370,25 +369,26 @@ bool gemm_tiled_large_accepts(const TiledGemmParams& p) {
     return (reinterpret_cast<uintptr_t>(p.y) & 15) == 0 && (p.ldy % 8) == 0 && (p.N % 8) == 0;
 }
 
+hipError_t setup_gemm_tiled_large() {
+    using namespace large;
+    static PerDeviceOnce once;
+    return once.run([] {
+        hipError_t e = allow_dynamic_lds((const void*)gemm_tiled_large_kernel<true>, kLdsBytes);
+        if (e != hipSuccess) return e;
+        return allow_dynamic_lds((const void*)gemm_tiled_large_kernel<false>, kLdsBytes);
+    });
+}
+
 hipError_t launch_gemm_tiled_large(const TiledGemmParams& p, hipStream_t stream) {
     using namespace large;
     if (!gemm_tiled_large_accepts(p)) return hipErrorInvalidValue;
-    static std::atomic<int> configured{0};
-    if (!configured.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_tiled_large_kernel<true>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void*)gemm_tiled_large_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kLdsBytes);
-        if (e != hipSuccess) return e;
-        configured.store(1, std::memory_order_release);
-    }
+    hipError_t e = setup_gemm_tiled_large();
+    if (e != hipSuccess) return e;
     const int tiles_m = (p.T + kBM - 1) / kBM, tiles_n = (p.N + kBN - 1) / kBN;
     const int total = tiles_m * tiles_n;
     dim3 grid((unsigned)(total < kNumCU ? total : kNumCU)), block(256);
-    if (p.out_bf16) hipLaunchKernelGGL(gemm_tiled_large_kernel<true>, grid, block, kLdsBytes, stream, p);
-    else hipLaunchKernelGGL(gemm_tiled_large_kernel<false>, grid, block, kLdsBytes, stream, p);
-    return hipGetLastError();
+    return p.out_bf16 ? launch(gemm_tiled_large_kernel<true>, grid, block, kLdsBytes, stream, p)
+                      : launch(gemm_tiled_large_kernel<false>, grid, block, kLdsBytes, stream, p);
 }
 
 }  // namespace duqpp

@@ -192,29 +192,24 @@ __global__ __launch_bounds__(256, STAGES == 3 ? 2 : 1) void gemm_tiled_small_ker
     }
 }
 
-template <int STAGES>
-static hipError_t launch_small(const TiledGemmParams& p, unsigned tiles, hipStream_t stream) {
-    constexpr int kLds = STAGES * kSStageBytes;
-    static std::atomic<int> configured{0};
-    if (!configured.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_tiled_small_kernel<true, STAGES>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+constexpr int kSLdsBytes = kSStages * kSStageBytes;
+
+hipError_t setup_gemm_tiled_small() {
+    static PerDeviceOnce once;
+    return once.run([] {
+        hipError_t e = allow_dynamic_lds((const void*)gemm_tiled_small_kernel<true, kSStages>, kSLdsBytes);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void*)gemm_tiled_small_kernel<false, STAGES>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-        if (e != hipSuccess) return e;
-        configured.store(1, std::memory_order_release);
-    }
-    dim3 grid(tiles), block(256);
-    if (p.out_bf16) hipLaunchKernelGGL((gemm_tiled_small_kernel<true, STAGES>), grid, block, kLds, stream, p);
-    else hipLaunchKernelGGL((gemm_tiled_small_kernel<false, STAGES>), grid, block, kLds, stream, p);
-    return hipGetLastError();
+        return allow_dynamic_lds((const void*)gemm_tiled_small_kernel<false, kSStages>, kSLdsBytes);
+    });
 }
 
 hipError_t launch_gemm_tiled_small(const TiledGemmParams& p, hipStream_t stream) {
+    hipError_t e = setup_gemm_tiled_small();
+    if (e != hipSuccess) return e;
     const int tiles_m = (p.T + kSBM - 1) / kSBM, tiles_n = (p.N + kSBN - 1) / kSBN;
-    const unsigned tiles = (unsigned)(tiles_m * tiles_n);
-    return launch_small<kSStages>(p, tiles, stream);
+    dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
+    return p.out_bf16 ? launch(gemm_tiled_small_kernel<true, kSStages>, grid, block, kSLdsBytes, stream, p)
+                      : launch(gemm_tiled_small_kernel<false, kSStages>, grid, block, kSLdsBytes, stream, p);
 }
 
 }  // namespace duqpp

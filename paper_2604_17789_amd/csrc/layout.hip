@@ -37,14 +37,12 @@ __global__ __launch_bounds__(256) void untile_kernel(LayoutParams p) {
 
 hipError_t launch_tile(const LayoutParams& p, hipStream_t stream) {
     const int64_t total = (int64_t)((p.rows + 31) / 32) * p.GP * 32;
-    hipLaunchKernelGGL(tile_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, p);
-    return hipGetLastError();
+    return launch(tile_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, p);
 }
 
 hipError_t launch_untile(const LayoutParams& p, hipStream_t stream) {
     const int64_t total = (int64_t)p.rows * p.G;
-    hipLaunchKernelGGL(untile_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, p);
-    return hipGetLastError();
+    return launch(untile_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, p);
 }
 
 }  // namespace duqpp

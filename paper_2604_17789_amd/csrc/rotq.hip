@@ -12,8 +12,6 @@
 // The quantiser uses the hardware E2M1 convert (v_cvt_scalef32_pk_fp4_f32), which rounds to
 // nearest even, saturates at 6, keeps the sign of zero and divides by the power of two held
 // in the exponent field of its scale operand (field 0 meaning 2^-127).
-#include <atomic>
-
 #include "duqpp_internal.h"
 
 namespace duqpp {
@@ -501,27 +499,27 @@ void plan_rotq(RotqParams& p) {
     p.ngroups = (p.ntiles + p.tiles_per_wg - 1) / p.tiles_per_wg;
 }
 
+hipError_t setup_rotq() {
+    static PerDeviceOnce once;
+    return once.run([] {
+        using TL = RotqTile<kRotqWaves, kRotqStages>;
+        constexpr int kWaveLdsMax = 8 * kWaveStages * kWaveTileBytes;
+        hipError_t e = allow_dynamic_lds((const void*)rotq_kernel<kRotqWaves, kRotqStages, false>, TL::kLdsBytes);
+        if (e != hipSuccess) return e;
+        return allow_dynamic_lds((const void*)rotq_wave_kernel<kWaveStages>, kWaveLdsMax);
+    });
+}
+
 hipError_t launch_rotq(const RotqParams& p, hipStream_t stream) {
     using TL = RotqTile<kRotqWaves, kRotqStages>;
-    static std::atomic<int> configured{0};
-    auto kern_rm = rotq_kernel<kRotqWaves, kRotqStages, false>;
-    auto kern_t = rotq_wave_kernel<kWaveStages>;
-    constexpr int kWaveLdsMax = 8 * kWaveStages * kWaveTileBytes;
-    if (!configured.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern_rm, hipFuncAttributeMaxDynamicSharedMemorySize, TL::kLdsBytes);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void*)kern_t, hipFuncAttributeMaxDynamicSharedMemorySize, kWaveLdsMax);
-        if (e != hipSuccess) return e;
-        configured.store(1, std::memory_order_release);
-    }
+    hipError_t e = setup_rotq();
+    if (e != hipSuccess) return e;
     dim3 grid((unsigned)((int64_t)p.nchunks * p.ngroups));
     if (p.tiled) {
         if (p.waves < 1 || p.waves > 8) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(kern_t, grid, dim3(p.waves * 64), p.waves * kWaveStages * kWaveTileBytes, stream, p);
-    } else {
-        hipLaunchKernelGGL(kern_rm, grid, dim3(kRotqWaves * 64), TL::kLdsBytes, stream, p);
+        return launch(rotq_wave_kernel<kWaveStages>, grid, dim3(p.waves * 64), p.waves * kWaveStages * kWaveTileBytes, stream, p);
     }
-    return hipGetLastError();
+    return launch(rotq_kernel<kRotqWaves, kRotqStages, false>, grid, dim3(kRotqWaves * 64), TL::kLdsBytes, stream, p);
 }
 
 // Test-only: the same quantize_group on fp32 values read from memory in the accumulator layout.
@@ -547,8 +545,7 @@ __global__ __launch_bounds__(64) void quant_dbg_kernel(QuantDbgParams p) {
 
 hipError_t launch_quant_dbg(const QuantDbgParams& p, hipStream_t stream) {
     dim3 grid((unsigned)p.G, (unsigned)((p.rows + 31) / 32)), block(64);
-    hipLaunchKernelGGL(quant_dbg_kernel, grid, block, 0, stream, p);
-    return hipGetLastError();
+    return launch(quant_dbg_kernel, grid, block, 0, stream, p);
 }
 
 }  // namespace duqpp

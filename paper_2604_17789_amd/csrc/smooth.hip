@@ -18,8 +18,7 @@ __global__ __launch_bounds__(256) void fold_smoothing_kernel(FoldParams p) {
 
 hipError_t launch_fold_smoothing(const FoldParams& p, hipStream_t stream) {
     const int64_t total = (int64_t)p.G * 1024;
-    hipLaunchKernelGGL(fold_smoothing_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, p);
-    return hipGetLastError();
+    return launch(fold_smoothing_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, p);
 }
 
 }  // namespace duqpp
