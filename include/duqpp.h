@@ -57,7 +57,8 @@ typedef enum {
     DUQPP_ERR_DTYPE = -4,     /* out_dtype is not a duqpp_dtype */
     DUQPP_ERR_WORKSPACE = -5, /* workspace missing or smaller than duqpp_gemm_workspace_bytes */
     DUQPP_ERR_ARCH = -6,      /* the current device is not gfx950 */
-    DUQPP_ERR_HIP = -7        /* a HIP runtime call or launch failed */
+    DUQPP_ERR_HIP = -7,       /* a HIP runtime call or launch failed */
+    DUQPP_ERR_TOO_LARGE = -8  /* duqpp_rotq_gemm_tiled_noalloc: the activations do not fit its fixed scratch */
 } duqpp_status;
 
 typedef enum { DUQPP_F32 = 0, DUQPP_BF16 = 1 } duqpp_dtype;
@@ -206,6 +207,25 @@ int duqpp_rotq_gemm_tiled(const void* x_bf16, int64_t ldx, const float* R, int64
                           int64_t T, int64_t N, int64_t K,
                           void* y, int out_dtype, int64_t ldy,
                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * duqpp_rotq_gemm_tiled for callers that cannot allocate or cannot hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without the workspace), same
+ * checks, same kernels and bit-identical results; the activation operand between the two kernels lives in a
+ * fixed array of duqpp_noalloc_scratch_bytes() = 8 MiB that is part of the library's device code (one copy per GPU,
+ * held until the process ends).  The call allocates and frees nothing.
+ *   - Limit: the two sizes duqpp_tiled_bytes(T, K) reports, each rounded up to 256, must fit the array (e.g.
+ *     T <= 1088 at K = 14336, T <= 544 at K = 28672); beyond it the call returns DUQPP_ERR_TOO_LARGE and
+ *     launches nothing.
+ *   - Every call on a GPU uses that GPU's one array: calls that may overlap on a GPU (different streams, several
+ *     host threads) race and must be ordered by the caller.  Nothing of an earlier call's contents is read.
+ *   - The array's device address is looked up once per device (at duqpp_init, else at the first call there).
+ */
+size_t duqpp_noalloc_scratch_bytes(void);   /* host, pure */
+int duqpp_rotq_gemm_tiled_noalloc(const void* x_bf16, int64_t ldx, const float* R, int64_t n_rblocks,
+                                  const uint8_t* b_codes_t, const uint8_t* b_scales_t,
+                                  int64_t T, int64_t N, int64_t K,
+                                  void* y, int out_dtype, int64_t ldy, void* stream);
 
 /*
  * Smoothing (Sec. 4.2, Eq. 3) merged into the rotation blocks, offline.  Eq. 5 in full is

@@ -22,6 +22,8 @@ from .binding import (  # noqa: F401
     mxfp4_gemm,
     mxfp4_gemm_tiled,
     init,
+    noalloc_scratch_bytes,
+    rotq_gemm_tiled_noalloc,
     quantize_weights_tiled,
     rotate_quantize_tiled,
     rotq_gemm_tiled,

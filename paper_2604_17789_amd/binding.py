@@ -59,6 +59,10 @@ def _load():
     L.duqpp_construct_rotation.restype = ci
     L.duqpp_init.argtypes = []
     L.duqpp_init.restype = ci
+    L.duqpp_noalloc_scratch_bytes.argtypes = []
+    L.duqpp_noalloc_scratch_bytes.restype = sz
+    L.duqpp_rotq_gemm_tiled_noalloc.argtypes = [vp, i64, fp, i64, u8p, u8p, i64, i64, i64, vp, ci, i64, vp]
+    L.duqpp_rotq_gemm_tiled_noalloc.restype = ci
     for name in ("duqpp_tiled_bytes", "duqpp_tile_operand", "duqpp_untile_operand", "duqpp_quantize_weights_tiled",
                  "duqpp_rotate_quantize_tiled", "duqpp_mxfp4_gemm_tiled", "duqpp_rotq_gemm_tiled",
                  "duqpp_fold_smoothing"):
@@ -324,6 +328,29 @@ def rotq_gemm_tiled(x, R, b_codes_t, b_scales_t, N, out_dtype=F32, out=None, wor
     _check(lib.duqpp_rotq_gemm_tiled(x.data_ptr(), x.stride(0), R.data_ptr(), _n_rblocks(R), b_codes_t.data_ptr(),
                                      b_scales_t.data_ptr(), T, N, K, y.data_ptr(), out_dtype, y.stride(0),
                                      workspace.data_ptr(), workspace.numel(), _stream()), "duqpp_rotq_gemm_tiled")
+    return y
+
+
+def noalloc_scratch_bytes():
+    return int(lib.duqpp_noalloc_scratch_bytes())
+
+
+def rotq_gemm_tiled_noalloc(x, R, b_codes_t, b_scales_t, N, out_dtype=F32, out=None):
+    """duqpp_rotq_gemm_tiled_noalloc: the fused call on the library's fixed scratch.  Pass `out` to keep this wrapper
+    from allocating the result."""
+    _dev(x, torch.bfloat16, "x")
+    _dev(R, torch.float32, "R")
+    _dev(b_codes_t, torch.uint8, "b_codes_t")
+    _dev(b_scales_t, torch.uint8, "b_scales_t")
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be [T, K] with unit stride along K")
+    T, K = x.shape
+    if (b_codes_t.numel(), b_scales_t.numel()) != tiled_bytes(N, K):
+        raise ValueError("weight operand sizes disagree with N, K")
+    y = _out(T, N, out_dtype, x.device, out)
+    _check(lib.duqpp_rotq_gemm_tiled_noalloc(x.data_ptr(), x.stride(0), R.data_ptr(), _n_rblocks(R), b_codes_t.data_ptr(),
+                                             b_scales_t.data_ptr(), T, N, K, y.data_ptr(), out_dtype, y.stride(0),
+                                             _stream()), "duqpp_rotq_gemm_tiled_noalloc")
     return y
 
 

@@ -5,6 +5,14 @@
 
 using namespace duqpp;
 
+// Scratch of duqpp_rotq_gemm_tiled_noalloc: the activation operand between its two kernels.  One copy per GPU,
+// held from the moment the library's code is loaded there until the process ends.  In host code the name is only a
+// handle for hipGetSymbolAddress; the device address it yields (g_scratch_ptr) is what kernels and copies are given.
+// (No `used` attribute: the compiler gives a static device variable that host code refers to external linkage in the
+// code object, which the runtime's look-up by name needs; `used` would keep it a local symbol.)
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) uint8_t scratch[kStaticScratchBytes];
+
 namespace {
 
 inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -24,6 +32,24 @@ int check_device() {
         g_arch_state[dev].store(st, std::memory_order_relaxed);
     }
     return st == 1 ? DUQPP_OK : DUQPP_ERR_ARCH;
+}
+
+// Device address of `scratch` on each device, looked up once per device with that device current.
+uint8_t* g_scratch_ptr[kMaxDevices];
+PerDeviceOnce g_scratch_once;
+
+hipError_t setup_scratch() {
+    return g_scratch_once.run([] {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = static_cast<uint8_t*>(ptr);
+        return hipSuccess;
+    });
 }
 
 int validate_rows_K(int64_t rows, int64_t K, int64_t ld, int64_t n_rblocks) {
@@ -99,9 +125,33 @@ int duqpp_init(void) {
     int st = check_device();
     if (st != DUQPP_OK) return st;
     if (setup_rotq() != hipSuccess || setup_gemm_tiled_mid() != hipSuccess || setup_gemm_tiled_small() != hipSuccess ||
-        setup_gemm_tiled_large() != hipSuccess)
+        setup_gemm_tiled_large() != hipSuccess || setup_scratch() != hipSuccess)
         return DUQPP_ERR_HIP;
     return DUQPP_OK;
+}
+
+size_t duqpp_noalloc_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int duqpp_rotq_gemm_tiled_noalloc(const void* x_bf16, int64_t ldx, const float* R, int64_t n_rblocks,
+                                  const uint8_t* b_codes_t, const uint8_t* b_scales_t, int64_t T, int64_t N, int64_t K,
+                                  void* y, int out_dtype, int64_t ldy, void* stream) {
+    if (!x_bf16 || !R || !b_codes_t || !b_scales_t || !y) return DUQPP_ERR_NULL;
+    int st = validate_rows_K(T, K, ldx, n_rblocks);
+    if (st != DUQPP_OK) return st;
+    const size_t cb = round256(tiled_codes_bytes(T, K / 32));
+    const size_t sb = round256(tiled_scales_bytes(T, K / 32));
+    if (cb + sb > kStaticScratchBytes) return DUQPP_ERR_TOO_LARGE;
+    st = check_device();
+    if (st != DUQPP_OK) return st;
+    if (setup_scratch() != hipSuccess) return DUQPP_ERR_HIP;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DUQPP_ERR_HIP;
+    uint8_t* a_codes = g_scratch_ptr[dev];                   // the device address, never the array's name
+    uint8_t* a_scales = a_codes + cb;
+    // The rotate+quantise kernel writes every byte of the operand the GEMM reads, padding included, so nothing of an
+    // earlier call's contents is read and nothing has to be cleared.
+    return rotq_gemm_tiled_impl(x_bf16, ldx, R, n_rblocks, a_codes, a_scales, b_codes_t, b_scales_t, T, N, K, y, out_dtype,
+                                ldy, stream);
 }
 
 int duqpp_validate_rotate_quantize(const void* x, int64_t T, int64_t K, int64_t ldx, const float* R,
@@ -367,6 +417,7 @@ const char* duqpp_status_string(int status) {
         case DUQPP_ERR_WORKSPACE: return "workspace missing or too small";
         case DUQPP_ERR_ARCH: return "device is not gfx950";
         case DUQPP_ERR_HIP: return "HIP runtime error";
+        case DUQPP_ERR_TOO_LARGE: return "problem exceeds the fixed scratch of the entry point that allocates nothing";
         default: return "unknown status";
     }
 }
