@@ -153,10 +153,11 @@ def main():
             if args.smoothing:                            # offline: diag(1/lambda) R for X, diag(lambda) R for W
                 Rd, Rw = duqpp.fold_smoothing(Rd, torch.from_numpy(lam).to(dev))
             bc, bs = duqpp.quantize_weights_tiled(w, Rw)  # offline weight transform (tiled layout), not timed
+            Rp = duqpp.pack_rotation(Rd)                  # offline: the activation-side blocks in the kernel's operand form
             del w, wb, xb
             cb, sb = duqpp.tiled_bytes(T, k)
             layers.append(dict(
-                name=nm, K=k, N=n, x=x, R=Rd, bc=bc, bs=bs,
+                name=nm, K=k, N=n, x=x, R=Rd, Rp=Rp, bc=bc, bs=bs,
                 ac=torch.empty(cb, dtype=torch.uint8, device=dev),
                 asc=torch.empty(sb, dtype=torch.uint8, device=dev),
                 ws=torch.empty(((cb + 255) // 256 + (sb + 255) // 256) * 256, dtype=torch.uint8, device=dev),
@@ -166,7 +167,7 @@ def main():
 
     # the timed path: activations rotated + quantised into the tiled operand layout, then the tiled GEMM
     def rotq1(l):
-        duqpp.rotate_quantize_tiled(l["x"], l["R"], out=(l["ac"], l["asc"]))
+        duqpp.rotate_quantize_tiled_packed(l["x"], l["Rp"], out=(l["ac"], l["asc"]))
 
     if args.zero_operands:
         for s_ in sets:
@@ -191,21 +192,25 @@ def main():
             rotq1(l)
             gemm1(l)
 
-    # the same step through the fused entry point (duqpp_rotq_gemm_tiled): one call per linear, the activation
+    # the same step through the fused entry point (duqpp_rotq_gemm_tiled_packed): one call per linear, the activation
     # operand in a caller-provided workspace
     def fused1(l):
-        duqpp.rotq_gemm_tiled(l["x"], l["R"], l["bc"], l["bs"], l["N"], out_dtype=out_dtype, out=l["y"], workspace=l["ws"])
+        duqpp.rotq_gemm_tiled_packed(l["x"], l["Rp"], l["bc"], l["bs"], l["N"], out_dtype=out_dtype, out=l["y"],
+                                     workspace=l["ws"])
 
     def fused_step(s):
         for l in s:
             fused1(l)
 
     # ---- timing ---------------------------------------------------------------------------
-    # `fn` is run args.steps times over the rotating buffer sets, bracketed by device synchronisation.  The
-    # launches are captured once into a HIP graph and the graph is replayed, so that the GPU runs them back to
-    # back: issued one by one from Python, launches of a ~10 us kernel measure the interpreter, not the kernel.
-    # (The kernels record no memset nodes.)  The figure from eager launches is kept beside it.  Events are
-    # recorded on the stream the kernels are launched on.
+    # `fn` is run args.steps times over the rotating buffer sets between two events on the launch stream, bracketed by
+    # device synchronisation, once as eager launches and once as a replayed HIP graph of the same launches (the kernels
+    # record no memset nodes).  Which of the two is the figure is fixed by the workload, see time_region.
+    # The chip's clock follows its power draw: the first few dozen launches after an idle stretch run 10-15 % faster
+    # than the sustained rate.  Every timed region is therefore preceded, without a pause, by at least kSustain untimed
+    # runs of the same work (more if --warmup asks for more), so that the figures are the sustained ones.
+    kSustain = 64
+    n_warm = max(args.warmup, kSustain)
     # How a graph of args.steps steps is timed: the graph is replayed twice back to back and the events bracket the
     # second replay.  The host enqueues the first event, the second replay and the last event while the GPU is still
     # busy with the first replay, so the events see exactly args.steps steps as the GPU runs them in steady state and
@@ -220,10 +225,9 @@ def main():
         return e0.elapsed_time(e1) * 1e3 / args.steps
 
     def time_region(fn, eager_only=False):
-        for i in range(min(args.warmup, 10)):
+        for i in range(n_warm):
             fn(sets[i % nsets])
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
         t0 = time.perf_counter()
         e0.record()
         for i in range(args.steps):
@@ -298,9 +302,9 @@ def main():
             print(f"bench.py: two-stream graph capture failed ({exc})", file=sys.stderr)
             return None
 
-    for i in range(args.warmup):
-        step(sets[i % nsets])
     if args.two_stream_child:
+        for i in range(n_warm):
+            step(sets[i % nsets])
         print(json.dumps({"two_stream_us": time_steps_two_streams()}))
         return
     whole = time_region(step, eager_only=args.eager)
@@ -326,9 +330,45 @@ def main():
         except Exception as exc:
             print(f"bench.py: two-stream child failed ({exc})", file=sys.stderr)
     ms_per_step = one_stream_us * 1e-3
+    # Each kernel alone in a loop (its launches back to back) ...
     tr = time_region(rotq, eager_only=args.eager)
     tg = time_region(gemm, eager_only=args.eager)
     rotq_us, rotq_eager_us, gemm_us, gemm_eager_us = tr["us"], tr["eager_us"], tg["us"], tg["eager_us"]
+    # ... and, for the prefill workloads, inside the timed steps themselves: the same eager launches with an event
+    # between the kernels, so that each kernel's share of the step (its run plus the gap to the next launch) is seen
+    # where it is timed -- alternating with the other kernel, as rocprofv3's kernel trace of this command sees it.
+    # These are the durations the rooflines use.
+    in_step = None
+    if T > 128:
+        for i in range(n_warm):
+            step(sets[i % nsets])
+        marks = []
+        for i in range(args.steps):
+            for l in sets[i % nsets]:
+                a, b, c = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+                a.record()
+                rotq1(l)
+                b.record()
+                gemm1(l)
+                c.record()
+                marks.append((a, b, c))
+        torch.cuda.synchronize()
+        in_step = {"rotq_us": sum(a.elapsed_time(b) for a, b, _ in marks) * 1e3 / args.steps,
+                   "gemm_us": sum(b.elapsed_time(c) for _, b, c in marks) * 1e3 / args.steps,
+                   "step_us": marks[0][0].elapsed_time(marks[-1][2]) * 1e3 / args.steps}
+        # what such a pair of events reads around next to nothing (a one-element fill): the launch gap and the events'
+        # own cost, contained in each figure above and not subtracted
+        tiny = torch.zeros(1, device=dev)
+        pairs = []
+        for i in range(64):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            tiny.zero_()
+            b.record()
+            pairs.append((a, b))
+        torch.cuda.synchronize()
+        in_step["empty_launch_between_events_us"] = sorted(a.elapsed_time(b) for a, b in pairs)[32] * 1e3
+        rotq_us, gemm_us = in_step["rotq_us"], in_step["gemm_us"]
     per_linear = None
     if not single:
         per_linear = []
@@ -365,19 +405,25 @@ def main():
         "config": {"workload": args.config, "T": T,
                    "linears": [{"name": nm, "K": k, "N": n} for nm, k, n, _ in linears],
                    "output": cfg["out"], "buffer_sets": nsets, "operand_layout": "tiled",
+                   "rotation_blocks": "packed offline (duqpp_pack_rotation)",
                    "smoothing": bool(args.smoothing)},
+        "per_kernel_timing": ("events between the kernels of the timed steps (eager launches); each figure contains the "
+                              "launch gap and the events' own cost, which read "
+                              f"{in_step['empty_launch_between_events_us']:.2f} us around a one-element fill; step with "
+                              f"those events: {in_step['step_us']:.2f} us") if in_step
+                             else "each kernel alone, its launches back to back in a replayed graph",
         "components": {
-            "rotate_quantize": {"us": round(rotq_us, 2), "us_eager_launches": round(rotq_eager_us, 2),
-                                "us_graph_replay": None if tr["graph_us"] is None else round(tr["graph_us"], 2),
+            "rotate_quantize": {"us": round(rotq_us, 2), "us_alone_eager_launches": round(rotq_eager_us, 2),
+                                "us_alone_graph_replay": None if tr["graph_us"] is None else round(tr["graph_us"], 2),
                                 "launches": len(linears), "GB/s": round(rotq_gbps, 1),
                                 "frac_hbm_peak": round(rotq_gbps / HBM_PEAK_GBPS, 4)},
-            "mxfp4_gemm": {"us": round(gemm_us, 2), "us_eager_launches": round(gemm_eager_us, 2),
-                           "us_graph_replay": None if tg["graph_us"] is None else round(tg["graph_us"], 2),
+            "mxfp4_gemm": {"us": round(gemm_us, 2), "us_alone_eager_launches": round(gemm_eager_us, 2),
+                           "us_alone_graph_replay": None if tg["graph_us"] is None else round(tg["graph_us"], 2),
                            "launches": len(linears), "TFLOP/s": round(gemm_tflops, 1),
                            "frac_mfma_peak": round(gemm_tflops / FP4_PEAK_TFLOPS, 4),
                            # N*K*(1/2 + 1/32) bytes of weights per launch: the decode-shape figure of merit
                            "weight_stream_GB/s": round(weight_bytes / (gemm_us * 1e-6) / 1e9, 1)},
-            # one duqpp_rotq_gemm_tiled call per linear (rotate+quantise into the caller's workspace, then the GEMM)
+            # one duqpp_rotq_gemm_tiled_packed call per linear (rotate+quantise into the caller's workspace, then the GEMM)
             # beside the two separate calls (ms_per_step): the same two kernels on the same stream either way
             "rotq_gemm_fused_call": {"us": round(fused["us"], 2), "us_eager_launches": round(fused["eager_us"], 2),
                                      "us_graph_replay": None if fused["graph_us"] is None else round(fused["graph_us"], 2),

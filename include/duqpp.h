@@ -129,6 +129,20 @@ int duqpp_rotq_gemm(const void* x_bf16, int64_t ldx, const float* R, int64_t n_r
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Offline: the rotation blocks in the form the tiled-output kernel consumes directly.  The blocks are calibrated
+ * offline like the weights (Sec. 4.2), so what every online launch would otherwise redo at its start -- fetching each
+ * 32 x 32 fp32 block and splitting every entry exactly into three bf16 pieces for the matrix cores (Eq. 4 / Eq. 5 at
+ * fp32 accuracy) -- is done once here.  Same pieces, so the *_packed calls below return bit for bit what their
+ * counterparts return for the fp32 blocks.
+ *   R         in   [n_rblocks, 32, 32] fp32 (any n_rblocks >= 1)
+ *   R_packed  out  duqpp_packed_rotation_bytes(n_rblocks) = 6144 * n_rblocks bytes, 16-byte aligned; per block
+ *                  [piece: low, middle, high][half of the 32 input channels][lane 0..63][8 bf16], lane (c + 32 h)
+ *                  holding R[16 s + 8 h + i][c] for i = 0..7 -- an opaque operand form, not an interchange format
+ */
+size_t duqpp_packed_rotation_bytes(int64_t n_rblocks);   /* host, pure; 0 for invalid arguments */
+int duqpp_pack_rotation(const float* R, int64_t n_rblocks, void* R_packed, void* stream);
+
+/*
  * TEST ONLY: runs the quantiser stage of duqpp_rotate_quantize (group amax, E8M0 scale,
  * E2M1 rounding, packing -- Eq. 2) on caller-supplied fp32 values, so that every fp32 bit
  * pattern can be swept through the device code.
@@ -169,6 +183,11 @@ int duqpp_rotate_quantize_tiled(const void* x_bf16, int64_t T, int64_t K, int64_
                                 const float* R, int64_t n_rblocks,
                                 uint8_t* x_codes_t, uint8_t* x_scales_t, void* stream);
 
+/* duqpp_rotate_quantize_tiled on packed rotation blocks (duqpp_pack_rotation; n_rblocks == K/32, or 1 for a shared block). */
+int duqpp_rotate_quantize_tiled_packed(const void* x_bf16, int64_t T, int64_t K, int64_t ldx,
+                                       const void* R_packed, int64_t n_rblocks,
+                                       uint8_t* x_codes_t, uint8_t* x_scales_t, void* stream);
+
 /* duqpp_mxfp4_gemm on tiled operands (no workspace). */
 int duqpp_mxfp4_gemm_tiled(const uint8_t* a_codes_t, const uint8_t* a_scales_t,
                            const uint8_t* b_codes_t, const uint8_t* b_scales_t,
@@ -207,6 +226,13 @@ int duqpp_rotq_gemm_tiled(const void* x_bf16, int64_t ldx, const float* R, int64
                           int64_t T, int64_t N, int64_t K,
                           void* y, int out_dtype, int64_t ldy,
                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* duqpp_rotq_gemm_tiled on packed rotation blocks. */
+int duqpp_rotq_gemm_tiled_packed(const void* x_bf16, int64_t ldx, const void* R_packed, int64_t n_rblocks,
+                                 const uint8_t* b_codes_t, const uint8_t* b_scales_t,
+                                 int64_t T, int64_t N, int64_t K,
+                                 void* y, int out_dtype, int64_t ldy,
+                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * duqpp_rotq_gemm_tiled for callers that cannot allocate or cannot hand over a workspace: code under HIP graph

@@ -22,6 +22,9 @@ from .binding import (  # noqa: F401
     mxfp4_gemm,
     mxfp4_gemm_tiled,
     init,
+    pack_rotation,
+    rotate_quantize_tiled_packed,
+    rotq_gemm_tiled_packed,
     noalloc_scratch_bytes,
     rotq_gemm_tiled_noalloc,
     quantize_weights_tiled,

@@ -59,6 +59,14 @@ def _load():
     L.duqpp_construct_rotation.restype = ci
     L.duqpp_init.argtypes = []
     L.duqpp_init.restype = ci
+    L.duqpp_packed_rotation_bytes.argtypes = [i64]
+    L.duqpp_packed_rotation_bytes.restype = sz
+    L.duqpp_pack_rotation.argtypes = [fp, i64, vp, vp]
+    L.duqpp_pack_rotation.restype = ci
+    L.duqpp_rotate_quantize_tiled_packed.argtypes = [vp, i64, i64, i64, vp, i64, u8p, u8p, vp]
+    L.duqpp_rotate_quantize_tiled_packed.restype = ci
+    L.duqpp_rotq_gemm_tiled_packed.argtypes = [vp, i64, vp, i64, u8p, u8p, i64, i64, i64, vp, ci, i64, vp, sz, vp]
+    L.duqpp_rotq_gemm_tiled_packed.restype = ci
     L.duqpp_noalloc_scratch_bytes.argtypes = []
     L.duqpp_noalloc_scratch_bytes.restype = sz
     L.duqpp_rotq_gemm_tiled_noalloc.argtypes = [vp, i64, fp, i64, u8p, u8p, i64, i64, i64, vp, ci, i64, vp]
@@ -285,6 +293,59 @@ def rotate_quantize_tiled(x, R, out=None):
 
 def quantize_weights_tiled(w, R, out=None):
     return _rows_op_tiled(lib.duqpp_quantize_weights_tiled, "duqpp_quantize_weights_tiled", w, R, out)
+
+
+PACKED_BLOCK_BYTES = 6144
+
+
+def pack_rotation(R):
+    """R fp32 [n, 32, 32] -> flat uint8 tensor of n * 6144 bytes: the blocks as the tiled-output kernel reads them."""
+    _dev(R, torch.float32, "R")
+    n = _n_rblocks(R)
+    nbytes = int(lib.duqpp_packed_rotation_bytes(n))
+    assert nbytes == n * PACKED_BLOCK_BYTES
+    out = torch.empty(nbytes, dtype=torch.uint8, device=R.device)
+    _check(lib.duqpp_pack_rotation(R.data_ptr(), n, out.data_ptr(), _stream()), "duqpp_pack_rotation")
+    return out
+
+
+def _n_packed(Rp):
+    _dev(Rp, torch.uint8, "R_packed")
+    if Rp.dim() != 1 or not Rp.is_contiguous() or Rp.numel() == 0 or Rp.numel() % PACKED_BLOCK_BYTES:
+        raise ValueError("R_packed must be the flat tensor pack_rotation returns")
+    return Rp.numel() // PACKED_BLOCK_BYTES
+
+
+def rotate_quantize_tiled_packed(x, R_packed, out=None):
+    """rotate_quantize_tiled on packed rotation blocks: same bytes out."""
+    _dev(x, torch.bfloat16, "x")
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be [rows, K] with unit stride along K")
+    rows, K = x.shape
+    ct, st_ = _tiled_buffers(rows, K, x.device, out)
+    _check(lib.duqpp_rotate_quantize_tiled_packed(x.data_ptr(), rows, K, x.stride(0), R_packed.data_ptr(), _n_packed(R_packed),
+                                                  ct.data_ptr(), st_.data_ptr(), _stream()), "duqpp_rotate_quantize_tiled_packed")
+    return ct, st_
+
+
+def rotq_gemm_tiled_packed(x, R_packed, b_codes_t, b_scales_t, N, out_dtype=F32, out=None, workspace=None):
+    _dev(x, torch.bfloat16, "x")
+    _dev(b_codes_t, torch.uint8, "b_codes_t")
+    _dev(b_scales_t, torch.uint8, "b_scales_t")
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be [T, K] with unit stride along K")
+    T, K = x.shape
+    if (b_codes_t.numel(), b_scales_t.numel()) != tiled_bytes(N, K):
+        raise ValueError("weight operand sizes disagree with N, K")
+    y = _out(T, N, out_dtype, x.device, out)
+    cb, sb = tiled_bytes(T, K)
+    if workspace is None:
+        workspace = torch.empty(((cb + 255) // 256 + (sb + 255) // 256) * 256, dtype=torch.uint8, device=x.device)
+    _check(lib.duqpp_rotq_gemm_tiled_packed(x.data_ptr(), x.stride(0), R_packed.data_ptr(), _n_packed(R_packed),
+                                            b_codes_t.data_ptr(), b_scales_t.data_ptr(), T, N, K, y.data_ptr(), out_dtype,
+                                            y.stride(0), workspace.data_ptr(), workspace.numel(), _stream()),
+           "duqpp_rotq_gemm_tiled_packed")
+    return y
 
 
 def gemm_kernel_for(T, N, K, out_dtype=F32):

@@ -60,12 +60,15 @@ int validate_rows_K(int64_t rows, int64_t K, int64_t ld, int64_t n_rblocks) {
     return DUQPP_OK;
 }
 
-int rotate_quantize_impl(const void* x, int64_t rows, int64_t K, int64_t ldx, const float* R, int64_t n_rblocks,
-                         uint8_t* codes, uint8_t* scales, float* ydbg, void* stream, bool tiled = false) {
-    int st = duqpp_validate_rotate_quantize(x, rows, K, ldx, R, n_rblocks, codes, scales);
+// R: fp32 blocks, or with `packed` the blocks in the form duqpp_pack_rotation writes (tiled output only).
+int rotate_quantize_impl(const void* x, int64_t rows, int64_t K, int64_t ldx, const void* R, int64_t n_rblocks,
+                         uint8_t* codes, uint8_t* scales, float* ydbg, void* stream, bool tiled = false,
+                         bool packed = false) {
+    int st = duqpp_validate_rotate_quantize(x, rows, K, ldx, static_cast<const float*>(R), n_rblocks, codes, scales);
     if (st != DUQPP_OK) return st;
     if (ydbg && !aligned_to(ydbg, 16)) return DUQPP_ERR_ALIGN;
     if (tiled && (!aligned_to(codes, 256) || !aligned_to(scales, 256))) return DUQPP_ERR_ALIGN;
+    if (packed && (!tiled || !aligned_to(R, 16))) return tiled ? DUQPP_ERR_ALIGN : DUQPP_ERR_SHAPE;
     st = check_device();
     if (st != DUQPP_OK) return st;
     RotqParams p{};
@@ -73,8 +76,9 @@ int rotate_quantize_impl(const void* x, int64_t rows, int64_t K, int64_t ldx, co
     p.ldx = ldx;
     p.rows = (int)rows;
     p.G = (int)(K / 32);
-    p.R = R;
-    p.r_stride = (n_rblocks == 1) ? 0 : 32 * 32;
+    p.R = static_cast<const float*>(R);
+    p.r_packed = packed ? 1 : 0;
+    p.r_stride = (n_rblocks == 1) ? 0 : (packed ? kPackedRotationBlockBytes : 32 * 32);
     p.codes = codes;
     p.scales = scales;
     p.ydbg = ydbg;
@@ -104,15 +108,16 @@ TiledScratch tiled_scratch(int64_t T, int64_t N, int64_t K) {
 
 // The fused call on tiled weights with the activation operand in a_codes / a_scales (256-byte aligned scratch of
 // the sizes duqpp_tiled_bytes reports): every argument of both stages is checked before the first launch.
-int rotq_gemm_tiled_impl(const void* x_bf16, int64_t ldx, const float* R, int64_t n_rblocks, uint8_t* a_codes,
+int rotq_gemm_tiled_impl(const void* x_bf16, int64_t ldx, const void* R, int64_t n_rblocks, uint8_t* a_codes,
                          uint8_t* a_scales, const uint8_t* b_codes_t, const uint8_t* b_scales_t, int64_t T, int64_t N,
-                         int64_t K, void* y, int out_dtype, int64_t ldy, void* stream) {
-    int st = duqpp_validate_rotate_quantize(x_bf16, T, K, ldx, R, n_rblocks, a_codes, a_scales);
+                         int64_t K, void* y, int out_dtype, int64_t ldy, void* stream, bool packed = false) {
+    int st = duqpp_validate_rotate_quantize(x_bf16, T, K, ldx, static_cast<const float*>(R), n_rblocks, a_codes, a_scales);
     if (st != DUQPP_OK) return st;
+    if (packed && !aligned_to(R, 16)) return DUQPP_ERR_ALIGN;
     st = duqpp_validate_mxfp4_gemm(a_codes, a_scales, b_codes_t, b_scales_t, T, N, K, y, out_dtype, ldy, nullptr, 0, 2);
     if (st != DUQPP_OK) return st;
     if (!aligned_to(b_codes_t, 256) || !aligned_to(b_scales_t, 256)) return DUQPP_ERR_ALIGN;
-    st = rotate_quantize_impl(x_bf16, T, K, ldx, R, n_rblocks, a_codes, a_scales, nullptr, stream, true);
+    st = rotate_quantize_impl(x_bf16, T, K, ldx, R, n_rblocks, a_codes, a_scales, nullptr, stream, true, packed);
     if (st != DUQPP_OK) return st;
     return duqpp_mxfp4_gemm_tiled(a_codes, a_scales, b_codes_t, b_scales_t, T, N, K, y, out_dtype, ldy, stream);
 }
@@ -369,6 +374,42 @@ int duqpp_rotq_gemm_tiled(const void* x_bf16, int64_t ldx, const float* R, int64
     uint8_t* a_scales = a_codes + cb;
     return rotq_gemm_tiled_impl(x_bf16, ldx, R, n_rblocks, a_codes, a_scales, b_codes_t, b_scales_t, T, N, K, y, out_dtype,
                                 ldy, stream);
+}
+
+size_t duqpp_packed_rotation_bytes(int64_t n_rblocks) {
+    if (n_rblocks < 1 || n_rblocks > (int64_t)1 << 25) return 0;
+    return (size_t)n_rblocks * kPackedRotationBlockBytes;
+}
+
+int duqpp_pack_rotation(const float* R, int64_t n_rblocks, void* R_packed, void* stream) {
+    if (!R || !R_packed) return DUQPP_ERR_NULL;
+    if (n_rblocks < 1 || n_rblocks > (int64_t)1 << 25) return DUQPP_ERR_SHAPE;
+    if (!aligned_to(R, 4) || !aligned_to(R_packed, 16)) return DUQPP_ERR_ALIGN;
+    int st = check_device();
+    if (st != DUQPP_OK) return st;
+    PackRotationParams p{R, static_cast<uint8_t*>(R_packed), (int)n_rblocks};
+    return launch_pack_rotation(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
+}
+
+int duqpp_rotate_quantize_tiled_packed(const void* x_bf16, int64_t T, int64_t K, int64_t ldx, const void* R_packed,
+                                       int64_t n_rblocks, uint8_t* x_codes_t, uint8_t* x_scales_t, void* stream) {
+    return rotate_quantize_impl(x_bf16, T, K, ldx, R_packed, n_rblocks, x_codes_t, x_scales_t, nullptr, stream, true, true);
+}
+
+int duqpp_rotq_gemm_tiled_packed(const void* x_bf16, int64_t ldx, const void* R_packed, int64_t n_rblocks,
+                                 const uint8_t* b_codes_t, const uint8_t* b_scales_t, int64_t T, int64_t N, int64_t K,
+                                 void* y, int out_dtype, int64_t ldy, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+    if (!x_bf16 || !R_packed || !b_codes_t || !b_scales_t || !y) return DUQPP_ERR_NULL;
+    int st = validate_rows_K(T, K, ldx, n_rblocks);
+    if (st != DUQPP_OK) return st;
+    const size_t cb = round256(tiled_codes_bytes(T, K / 32));
+    const size_t sb = round256(tiled_scales_bytes(T, K / 32));
+    if (!workspace || workspace_bytes < cb + sb) return DUQPP_ERR_WORKSPACE;
+    if (!aligned_to(workspace, 256)) return DUQPP_ERR_ALIGN;
+    uint8_t* a_codes = static_cast<uint8_t*>(workspace);
+    return rotq_gemm_tiled_impl(x_bf16, ldx, R_packed, n_rblocks, a_codes, a_codes + cb, b_codes_t, b_scales_t, T, N, K, y,
+                                out_dtype, ldy, stream, true);
 }
 
 int duqpp_fold_smoothing(const float* R, int64_t n_rblocks, const float* lambda, int64_t K, float* R_act,

@@ -65,8 +65,9 @@ struct RotqParams {
     int64_t ldx;
     int rows;
     int G;               // K / 32
-    const float* R;      // [n_rblocks, 32, 32]
-    int r_stride;        // floats between consecutive blocks of R (0 when one block is shared)
+    const float* R;      // [n_rblocks, 32, 32]; with r_packed the packed blocks of duqpp_pack_rotation
+    int r_stride;        // floats (bytes when r_packed) between consecutive blocks of R (0 when one block is shared)
+    int r_packed;        // R holds packed blocks (tiled output only)
     uint8_t* codes;      // [rows, K/2], or the tiled codes when tiled != 0
     uint8_t* scales;     // [rows, G], or the tiled scales
     int tiled;           // output placement
@@ -81,6 +82,12 @@ struct RotqParams {
 };
 hipError_t launch_rotq(const RotqParams& p, hipStream_t stream);
 void plan_rotq(RotqParams& p);    // fills ntiles / tiles_per_wg / ngroups / nchunks / waves / by_columns
+
+constexpr int kPackedRotationBlockBytes = 6144;   // three bf16 pieces of a 32 x 32 block
+struct PackRotationParams {
+    const float* R; uint8_t* packed; int n_blocks;
+};
+hipError_t launch_pack_rotation(const PackRotationParams& p, hipStream_t stream);
 
 struct QuantDbgParams {
     const float* y; int64_t ldy; int rows; int G; uint8_t* codes; uint8_t* scales;

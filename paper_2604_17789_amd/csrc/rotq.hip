@@ -65,6 +65,22 @@ __device__ __forceinline__ void load_rot_operand(const float* __restrict__ Rb, i
     }
 }
 
+// The same operand from the packed form duqpp_pack_rotation writes offline (the blocks are calibrated offline,
+// Sec. 4.2, like the weights): per block 6 KiB as [piece: lo, mid, hi][k-step][lane][8 bf16], i.e. each of the six
+// registers quads of a lane is one 16-byte load and a wave-level load is one contiguous KiB.  No split, no strided
+// 4-byte loads at the head of every launch.
+constexpr int kPackedBlockBytes = 3 * 2 * 64 * 16;
+static_assert(kPackedBlockBytes == kPackedRotationBlockBytes, "size the ABI reports for a packed block");
+__device__ __forceinline__ void load_rot_operand_packed(const uint8_t* __restrict__ Pb, int lane, RotOperand& op) {
+    const u32x4* q = (const u32x4*)Pb + lane;
+    op.lo[0] = __builtin_bit_cast(bf16x8, q[0 * 64]);
+    op.lo[1] = __builtin_bit_cast(bf16x8, q[1 * 64]);
+    op.mid[0] = __builtin_bit_cast(bf16x8, q[2 * 64]);
+    op.mid[1] = __builtin_bit_cast(bf16x8, q[3 * 64]);
+    op.hi[0] = __builtin_bit_cast(bf16x8, q[4 * 64]);
+    op.hi[1] = __builtin_bit_cast(bf16x8, q[5 * 64]);
+}
+
 // acc[i] of lane (t = lane & 31, h) is y[token t][channel 8 (i / 4) + 4 h + i % 4] of one block.
 __device__ __forceinline__ f32x16 rotate_tile(const RotOperand& op, const u32x4 xv[2]) {
     f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -395,7 +411,7 @@ __device__ __forceinline__ void issue_wave_tile(const RotqParams& p, uint32_t ld
     }
 }
 
-template <int STAGES>
+template <int STAGES, bool PACKED>
 __global__ __launch_bounds__(512) void rotq_wave_kernel(RotqParams p) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     int logical;
@@ -430,8 +446,14 @@ __global__ __launch_bounds__(512) void rotq_wave_kernel(RotqParams p) {
         if (tile0 + d < tile1) issue_wave_tile(p, ring + d * kWaveTileBytes, tile0 + d, pair, lane);
     // the rotation blocks arrive behind the first tiles instead of ahead of them
     RotOperand op0, op1;
-    load_rot_operand(p.R + (int64_t)j0 * p.r_stride, c, h, op0);
-    load_rot_operand(p.R + (int64_t)j1 * p.r_stride, c, h, op1);
+    if constexpr (PACKED) {
+        const uint8_t* rp = (const uint8_t*)p.R;
+        load_rot_operand_packed(rp + (int64_t)j0 * p.r_stride, lane, op0);
+        load_rot_operand_packed(rp + (int64_t)j1 * p.r_stride, lane, op1);
+    } else {
+        load_rot_operand(p.R + (int64_t)j0 * p.r_stride, c, h, op0);
+        load_rot_operand(p.R + (int64_t)j1 * p.r_stride, c, h, op1);
+    }
 
     int stage = 0;
     for (int tile = tile0; tile < tile1; ++tile) {
@@ -481,6 +503,21 @@ void plan_rotq(RotqParams& p) {
         const int npairs = p.GP / 2;
         p.waves = 8;
         while (p.waves > 1 && (int64_t)((npairs + p.waves - 1) / p.waves) * p.ntiles < kNumCU) p.waves /= 2;
+        if (p.waves == 8) {
+            // Enough work for every CU: 5 to 8 waves per workgroup, whichever leaves the busiest CU the fewest
+            // (wave, tile) units in the one resident round; more waves when equal.  K = 14336 has 224 block pairs:
+            // 8 waves give 28 column chunks x 8 token runs = 224 workgroups on 256 CUs, 7 waves 32 x 8 = 256.
+            int64_t best = -1;
+            for (int w = 8; w >= 5; --w) {
+                const int nch = (npairs + w - 1) / w;
+                int groups = kNumCU / nch;
+                groups = groups < 1 ? 1 : (groups > p.ntiles ? p.ntiles : groups);
+                const int per = (p.ntiles + groups - 1) / groups;
+                const int64_t wgs = (int64_t)nch * ((p.ntiles + per - 1) / per);
+                const int64_t cost = (int64_t)w * per * ((wgs + kNumCU - 1) / kNumCU);
+                if (best < 0 || cost < best) { best = cost; p.waves = w; }
+            }
+        }
         p.nchunks = (npairs + p.waves - 1) / p.waves;
         p.by_columns = p.nchunks >= 3 * kNumXCD;
     } else {
@@ -489,7 +526,7 @@ void plan_rotq(RotqParams& p) {
     }
     // One resident round: each wave keeps its R blocks in registers and walks as many token
     // tiles as the problem allows, so the fetch and split of R is amortised.
-    const int64_t slots = (int64_t)kNumCU * kRotqWGPerCU * (kRotqWaves / p.waves);
+    const int64_t slots = (int64_t)kNumCU * kRotqWGPerCU * (p.waves >= 5 ? 1 : kRotqWaves / p.waves);
     int groups = (int)(slots / p.nchunks);
     if (groups < 1) groups = 1;
     if (groups > p.ntiles) groups = p.ntiles;
@@ -506,7 +543,9 @@ hipError_t setup_rotq() {
         constexpr int kWaveLdsMax = 8 * kWaveStages * kWaveTileBytes;
         hipError_t e = allow_dynamic_lds((const void*)rotq_kernel<kRotqWaves, kRotqStages, false>, TL::kLdsBytes);
         if (e != hipSuccess) return e;
-        return allow_dynamic_lds((const void*)rotq_wave_kernel<kWaveStages>, kWaveLdsMax);
+        e = allow_dynamic_lds((const void*)rotq_wave_kernel<kWaveStages, false>, kWaveLdsMax);
+        if (e != hipSuccess) return e;
+        return allow_dynamic_lds((const void*)rotq_wave_kernel<kWaveStages, true>, kWaveLdsMax);
     });
 }
 
@@ -517,9 +556,31 @@ hipError_t launch_rotq(const RotqParams& p, hipStream_t stream) {
     dim3 grid((unsigned)((int64_t)p.nchunks * p.ngroups));
     if (p.tiled) {
         if (p.waves < 1 || p.waves > 8) return hipErrorInvalidValue;
-        return launch(rotq_wave_kernel<kWaveStages>, grid, dim3(p.waves * 64), p.waves * kWaveStages * kWaveTileBytes, stream, p);
+        const size_t lds = (size_t)p.waves * kWaveStages * kWaveTileBytes;
+        return p.r_packed ? launch(rotq_wave_kernel<kWaveStages, true>, grid, dim3(p.waves * 64), lds, stream, p)
+                          : launch(rotq_wave_kernel<kWaveStages, false>, grid, dim3(p.waves * 64), lds, stream, p);
     }
+    if (p.r_packed) return hipErrorInvalidValue;             // the packed blocks feed the tiled-output kernel only
     return launch(rotq_kernel<kRotqWaves, kRotqStages, false>, grid, dim3(kRotqWaves * 64), TL::kLdsBytes, stream, p);
+}
+
+// Offline: the rotation blocks in the packed form load_rot_operand_packed reads.  One wave per block; the pieces are
+// made by the very code the unpacked kernels run at their start, so both forms rotate with the same bits.
+__global__ __launch_bounds__(64) void pack_rotation_kernel(PackRotationParams p) {
+    const int lane = threadIdx.x, c = lane & 31, h = lane >> 5;
+    RotOperand op;
+    load_rot_operand(p.R + (int64_t)blockIdx.x * 1024, c, h, op);
+    u32x4* q = (u32x4*)(p.packed + (int64_t)blockIdx.x * kPackedBlockBytes) + lane;
+    q[0 * 64] = __builtin_bit_cast(u32x4, op.lo[0]);
+    q[1 * 64] = __builtin_bit_cast(u32x4, op.lo[1]);
+    q[2 * 64] = __builtin_bit_cast(u32x4, op.mid[0]);
+    q[3 * 64] = __builtin_bit_cast(u32x4, op.mid[1]);
+    q[4 * 64] = __builtin_bit_cast(u32x4, op.hi[0]);
+    q[5 * 64] = __builtin_bit_cast(u32x4, op.hi[1]);
+}
+
+hipError_t launch_pack_rotation(const PackRotationParams& p, hipStream_t stream) {
+    return launch(pack_rotation_kernel, dim3((unsigned)p.n_blocks), dim3(64), 0, stream, p);
 }
 
 // Test-only: the same quantize_group on fp32 values read from memory in the accumulator layout.
