@@ -312,6 +312,12 @@ def main():
     # one-stream graph replay for the decode ones): the figure the result line's value is computed from
     one_stream_us = whole["us"]
     fused = time_region(fused_step, eager_only=args.eager)
+    # up to 32 tokens: the one-kernel form (rotation and quantiser in the prologue of every product workgroup)
+    one_kernel = None
+    if T <= 32:
+        one_kernel = time_region(lambda s: [duqpp.rotq_gemm_fused_decode(l["x"], l["Rp"], l["bc"], l["bs"], l["N"],
+                                                                         out_dtype=out_dtype, out=l["y"]) for l in s],
+                                 eager_only=args.eager)
     # A second launch form is reported beside it, never as the metric: the same steps as a graph over two streams.  It
     # is measured in a child process of its own (same inputs, same kernels), so that nothing that happens to a capture
     # over several streams can cost this run its result line.  Prefill workloads only.
@@ -440,6 +446,11 @@ def main():
                                      "traffic": MEASURED_TRAFFIC["rotq"] if headline else None,
                                      "traffic_source": TRAFFIC_SOURCE if headline else None},
     }
+    if one_kernel is not None:
+        # duqpp_rotq_gemm_fused_decode: one launch, no activation operand in memory; every workgroup repeats the rotation
+        result["components"]["rotq_gemm_one_kernel"] = {"us": round(one_kernel["us"], 2),
+                                                        "us_eager_launches": round(one_kernel["eager_us"], 2),
+                                                        "two_launches_us": round(one_stream_us, 2)}
     if per_linear:
         result["components"]["per_linear"] = per_linear
         # each per-linear loop cycles the buffer sets of ONE linear; the aggregate figures above cycle all of them

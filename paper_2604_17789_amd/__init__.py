@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     pack_rotation,
     rotate_quantize_tiled_packed,
     rotq_gemm_tiled_packed,
+    rotq_gemm_fused_decode,
     noalloc_scratch_bytes,
     rotq_gemm_tiled_noalloc,
     quantize_weights_tiled,

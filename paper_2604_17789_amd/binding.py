@@ -67,6 +67,8 @@ def _load():
     L.duqpp_rotate_quantize_tiled_packed.restype = ci
     L.duqpp_rotq_gemm_tiled_packed.argtypes = [vp, i64, vp, i64, u8p, u8p, i64, i64, i64, vp, ci, i64, vp, sz, vp]
     L.duqpp_rotq_gemm_tiled_packed.restype = ci
+    L.duqpp_rotq_gemm_fused_decode.argtypes = [vp, i64, vp, i64, u8p, u8p, i64, i64, i64, vp, ci, i64, u8p, u8p, vp]
+    L.duqpp_rotq_gemm_fused_decode.restype = ci
     L.duqpp_noalloc_scratch_bytes.argtypes = []
     L.duqpp_noalloc_scratch_bytes.restype = sz
     L.duqpp_rotq_gemm_tiled_noalloc.argtypes = [vp, i64, fp, i64, u8p, u8p, i64, i64, i64, vp, ci, i64, vp]
@@ -346,6 +348,26 @@ def rotq_gemm_tiled_packed(x, R_packed, b_codes_t, b_scales_t, N, out_dtype=F32,
                                             y.stride(0), workspace.data_ptr(), workspace.numel(), _stream()),
            "duqpp_rotq_gemm_tiled_packed")
     return y
+
+
+def rotq_gemm_fused_decode(x, R_packed, b_codes_t, b_scales_t, N, out_dtype=F32, out=None, return_operand=False):
+    """The one-kernel form (T <= 32).  return_operand: also the activation codes / scales (tiled) it was formed from."""
+    _dev(x, torch.bfloat16, "x")
+    _dev(b_codes_t, torch.uint8, "b_codes_t")
+    _dev(b_scales_t, torch.uint8, "b_scales_t")
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be [T, K] with unit stride along K")
+    T, K = x.shape
+    if (b_codes_t.numel(), b_scales_t.numel()) != tiled_bytes(N, K):
+        raise ValueError("weight operand sizes disagree with N, K")
+    y = _out(T, N, out_dtype, x.device, out)
+    ct, st_ = _tiled_buffers(T, K, x.device) if return_operand else (None, None)
+    _check(lib.duqpp_rotq_gemm_fused_decode(x.data_ptr(), x.stride(0), R_packed.data_ptr(), _n_packed(R_packed),
+                                            b_codes_t.data_ptr(), b_scales_t.data_ptr(), T, N, K, y.data_ptr(), out_dtype,
+                                            y.stride(0), ct.data_ptr() if return_operand else None,
+                                            st_.data_ptr() if return_operand else None, _stream()),
+           "duqpp_rotq_gemm_fused_decode")
+    return (y, ct, st_) if return_operand else y
 
 
 def gemm_kernel_for(T, N, K, out_dtype=F32):

@@ -412,6 +412,28 @@ int duqpp_rotq_gemm_tiled_packed(const void* x_bf16, int64_t ldx, const void* R_
                                 out_dtype, ldy, stream, true);
 }
 
+int duqpp_rotq_gemm_fused_decode(const void* x_bf16, int64_t ldx, const void* R_packed, int64_t n_rblocks,
+                                 const uint8_t* b_codes_t, const uint8_t* b_scales_t, int64_t T, int64_t N, int64_t K,
+                                 void* y, int out_dtype, int64_t ldy, uint8_t* a_codes_t_dbg, uint8_t* a_scales_t_dbg,
+                                 void* stream) {
+    if (!x_bf16 || !R_packed || !b_codes_t || !b_scales_t || !y) return DUQPP_ERR_NULL;
+    if ((a_codes_t_dbg == nullptr) != (a_scales_t_dbg == nullptr)) return DUQPP_ERR_NULL;
+    int st = validate_rows_K(T, K, ldx, n_rblocks);
+    if (st != DUQPP_OK) return st;
+    if (T > 32 || N < 1 || N > (int64_t)1 << 30 || ldy < N) return DUQPP_ERR_SHAPE;
+    if (out_dtype != DUQPP_F32 && out_dtype != DUQPP_BF16) return DUQPP_ERR_DTYPE;
+    if (!aligned_to(x_bf16, 16) || (ldx % 8) != 0 || !aligned_to(R_packed, 16) || !aligned_to(b_codes_t, 256) ||
+        !aligned_to(b_scales_t, 256) || !aligned_to(y, out_dtype == DUQPP_F32 ? 4 : 2) ||
+        (a_codes_t_dbg && (!aligned_to(a_codes_t_dbg, 256) || !aligned_to(a_scales_t_dbg, 256))))
+        return DUQPP_ERR_ALIGN;
+    st = check_device();
+    if (st != DUQPP_OK) return st;
+    FusedDecodeParams p{static_cast<const uint16_t*>(x_bf16), ldx, (int)T, static_cast<const uint8_t*>(R_packed),
+                        n_rblocks == 1 ? 0 : kPackedRotationBlockBytes, b_codes_t, b_scales_t, (int)N, (int)(K / 32),
+                        (int)tiled_groups(K / 32), y, ldy, out_dtype == DUQPP_BF16, a_codes_t_dbg, a_scales_t_dbg};
+    return launch_rotq_gemm_fused_decode(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
+}
+
 int duqpp_fold_smoothing(const float* R, int64_t n_rblocks, const float* lambda, int64_t K, float* R_act,
                          float* R_wgt, void* stream) {
     if (!R || !lambda || !R_act || !R_wgt) return DUQPP_ERR_NULL;

@@ -159,6 +159,17 @@ hipError_t launch_gemm_tiled_as(const TiledGemmParams& p, int kernel, hipStream_
 hipError_t launch_gemm_tiled_small(const TiledGemmParams& p, hipStream_t stream);   // 64 x 128 tiles
 hipError_t launch_gemm_tiled_large(const TiledGemmParams& p, hipStream_t stream);   // 256 x 256 tiles
 bool gemm_tiled_large_accepts(const TiledGemmParams& p);                           // output alignment the large kernel needs
+// ---- one-kernel rotate + quantise + multiply for up to 32 tokens (rotq_gemm_fused.hip) ----------------------
+struct FusedDecodeParams {
+    const uint16_t* x; int64_t ldx; int T;               // bf16 [T, K]
+    const uint8_t* r_packed; int r_stride;                // packed rotation blocks; bytes between them (0 = one shared block)
+    const uint8_t* b_codes; const uint8_t* b_scales;      // tiled weights
+    int N, G, GP;
+    void* y; int64_t ldy; int out_bf16;
+    uint8_t* dbg_codes; uint8_t* dbg_scales;              // nullable: the activation operand (tiled, one row tile)
+};
+hipError_t launch_rotq_gemm_fused_decode(const FusedDecodeParams& p, hipStream_t stream);
+
 constexpr int kDecodeMaxT = 128;   // up to four activation row tiles go to the weight-streaming kernel
 hipError_t launch_gemm_decode(const TiledGemmParams& p, hipStream_t stream);    // T <= kDecodeMaxT
 
