@@ -204,25 +204,29 @@ def main():
 
     # ---- timing ---------------------------------------------------------------------------
     # `fn` is run args.steps times over the rotating buffer sets between two events on the launch stream, bracketed by
-    # device synchronisation, once as eager launches and once as a replayed HIP graph of the same launches (the kernels
-    # record no memset nodes).  Which of the two is the figure is fixed by the workload, see time_region.
+    # device synchronisation.  The figure comes from a HIP graph of exactly those launches (the kernels record no memset
+    # nodes): issued one by one from Python, launches of a 3-10 us kernel measure the interpreter, and a graph is never
+    # bound by the host.  The figure of eager launches is kept beside it.
     # The chip's clock follows its power draw: the first few dozen launches after an idle stretch run 10-15 % faster
-    # than the sustained rate.  Every timed region is therefore preceded, without a pause, by at least kSustain untimed
-    # runs of the same work (more if --warmup asks for more), so that the figures are the sustained ones.
-    kSustain = 64
+    # than the sustained rate, and any single reading moves by several per cent with what ran before it.  Every timed
+    # region is therefore preceded, without a pause, by at least kSustain untimed runs of the same work (more if
+    # --warmup asks for more), and the graph is replayed kReps + 1 times back to back, each replay of exactly args.steps
+    # steps between its own pair of events; the figure is the median of the last kReps.  The host enqueues all replays
+    # while the GPU is busy with the first, so none of them contains the host's latency of launching a graph (some
+    # 100 us: 5-10 us per step when only 20 steps are timed).
+    kSustain, kReps = 64, 5
     n_warm = max(args.warmup, kSustain)
-    # How a graph of args.steps steps is timed: the graph is replayed twice back to back and the events bracket the
-    # second replay.  The host enqueues the first event, the second replay and the last event while the GPU is still
-    # busy with the first replay, so the events see exactly args.steps steps as the GPU runs them in steady state and
-    # not the host's latency of launching a graph (some 100 us: 5-10 us per step when only 20 steps are timed).
+
     def time_replay(g):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        g.replay()
-        e0.record()
-        g.replay()
-        e1.record()
+        marks = []
+        for _ in range(kReps + 1):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.replay()
+            e1.record()
+            marks.append((e0, e1))
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / args.steps
+        return sorted(a.elapsed_time(b) for a, b in marks[1:])[kReps // 2] * 1e3 / args.steps
 
     def time_region(fn, eager_only=False):
         for i in range(n_warm):
@@ -256,10 +260,7 @@ def main():
                 graph_us = time_replay(g)
             except Exception as exc:  # capture unavailable: keep the eager figures
                 print(f"bench.py: graph capture failed ({exc}); using eager launches", file=sys.stderr)
-        # Which form is the figure, by rule and not by outcome: kernels of a prefill workload run for 15 us and more, the
-        # host stays ahead of the GPU and eager launches are the plain case; with a handful of tokens a Python launch
-        # (10 us) outlasts the kernel, so only a replayed graph shows the kernels.  The other form is reported beside it.
-        use_graph = graph_us is not None and T <= 128
+        use_graph = graph_us is not None
         return dict(us=graph_us if use_graph else eager_us, eager_us=eager_us, graph_us=graph_us,
                     wall_us=graph_wall_us if graph_wall_us is not None else eager_wall_us,
                     eager_wall_us=eager_wall_us, graph=use_graph)
@@ -308,8 +309,8 @@ def main():
         print(json.dumps({"two_stream_us": time_steps_two_streams()}))
         return
     whole = time_region(step, eager_only=args.eager)
-    # exactly args.steps steps between two events on the launch stream (eager launches for the prefill workloads, a
-    # one-stream graph replay for the decode ones): the figure the result line's value is computed from
+    # exactly args.steps steps between two events on the launch stream (a one-stream graph replay; eager launches with
+    # --eager): the figure the result line's value is computed from
     one_stream_us = whole["us"]
     fused = time_region(fused_step, eager_only=args.eager)
     # up to 32 tokens: the one-kernel form (rotation and quantiser in the prologue of every product workgroup)
@@ -336,45 +337,11 @@ def main():
         except Exception as exc:
             print(f"bench.py: two-stream child failed ({exc})", file=sys.stderr)
     ms_per_step = one_stream_us * 1e-3
-    # Each kernel alone in a loop (its launches back to back) ...
+    # each kernel alone, its launches back to back (what the rooflines use; includes the ~2.2 us launch-to-launch gap an
+    # empty kernel also shows)
     tr = time_region(rotq, eager_only=args.eager)
     tg = time_region(gemm, eager_only=args.eager)
     rotq_us, rotq_eager_us, gemm_us, gemm_eager_us = tr["us"], tr["eager_us"], tg["us"], tg["eager_us"]
-    # ... and, for the prefill workloads, inside the timed steps themselves: the same eager launches with an event
-    # between the kernels, so that each kernel's share of the step (its run plus the gap to the next launch) is seen
-    # where it is timed -- alternating with the other kernel, as rocprofv3's kernel trace of this command sees it.
-    # These are the durations the rooflines use.
-    in_step = None
-    if T > 128:
-        for i in range(n_warm):
-            step(sets[i % nsets])
-        marks = []
-        for i in range(args.steps):
-            for l in sets[i % nsets]:
-                a, b, c = (torch.cuda.Event(enable_timing=True) for _ in range(3))
-                a.record()
-                rotq1(l)
-                b.record()
-                gemm1(l)
-                c.record()
-                marks.append((a, b, c))
-        torch.cuda.synchronize()
-        in_step = {"rotq_us": sum(a.elapsed_time(b) for a, b, _ in marks) * 1e3 / args.steps,
-                   "gemm_us": sum(b.elapsed_time(c) for _, b, c in marks) * 1e3 / args.steps,
-                   "step_us": marks[0][0].elapsed_time(marks[-1][2]) * 1e3 / args.steps}
-        # what such a pair of events reads around next to nothing (a one-element fill): the launch gap and the events'
-        # own cost, contained in each figure above and not subtracted
-        tiny = torch.zeros(1, device=dev)
-        pairs = []
-        for i in range(64):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            tiny.zero_()
-            b.record()
-            pairs.append((a, b))
-        torch.cuda.synchronize()
-        in_step["empty_launch_between_events_us"] = sorted(a.elapsed_time(b) for a, b in pairs)[32] * 1e3
-        rotq_us, gemm_us = in_step["rotq_us"], in_step["gemm_us"]
     per_linear = None
     if not single:
         per_linear = []
@@ -403,7 +370,8 @@ def main():
         "ms_per_step_graph_replay": None if whole["graph_us"] is None else round(whole["graph_us"] * 1e-3, 5),
         "ms_per_step_graph_replay_host_clock": round(whole["wall_us"] * 1e-3, 5),
         "ms_per_step_two_stream_graph": None if two_stream_us is None else round(two_stream_us * 1e-3, 5),
-        "launch": ("HIP graph replay of the timed steps on one stream (decode workload), timed by events on that stream"
+        "launch": ("HIP graph replay of the timed steps on one stream, timed by events on that stream (median of "
+                   f"{kReps} back-to-back replays after {n_warm} untimed steps)"
                    if whole["graph"] else "eager launches on one stream, timed by events on that stream"),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "mxfp4 (E2M1 codes + E8M0 scales; fp32 rotation and accumulation)",
@@ -413,11 +381,7 @@ def main():
                    "output": cfg["out"], "buffer_sets": nsets, "operand_layout": "tiled",
                    "rotation_blocks": "packed offline (duqpp_pack_rotation)",
                    "smoothing": bool(args.smoothing)},
-        "per_kernel_timing": ("events between the kernels of the timed steps (eager launches); each figure contains the "
-                              "launch gap and the events' own cost, which read "
-                              f"{in_step['empty_launch_between_events_us']:.2f} us around a one-element fill; step with "
-                              f"those events: {in_step['step_us']:.2f} us") if in_step
-                             else "each kernel alone, its launches back to back in a replayed graph",
+        "per_kernel_timing": "each kernel alone, its launches back to back in a replayed graph (median of replays)",
         "components": {
             "rotate_quantize": {"us": round(rotq_us, 2), "us_alone_eager_launches": round(rotq_eager_us, 2),
                                 "us_alone_graph_replay": None if tr["graph_us"] is None else round(tr["graph_us"], 2),
