@@ -27,7 +27,7 @@ FP4_PEAK_TFLOPS = 10100.0     # MI355X dense MXFP4 matrix peak, published (256 C
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE (x 2.000) + WRITE_SIZE (x 1.000), the factors a plain
 # 256 MiB device copy gives for the same counters; workload c2_8b_down_prefill.  Counter runs are separate runs of
 # this script under the profiler: the figures are copied from their summary, not measured by the run that prints them.
-MEASURED_TRAFFIC = {"gemm": 125.12e6 + 16.79e6, "rotq": 60.93e6 + 15.60e6}
+MEASURED_TRAFFIC = {"gemm": 125.12e6 + 16.78e6, "rotq": 61.56e6 + 15.60e6}
 TRAFFIC_SOURCE = ("profiles/gemm_tiled_and_rotq_c2_8b_down_prefill_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE and "
                   "WRITE_SIZE runs of this workload, scaled by a plain copy's readings); not measured in this run")
 
@@ -45,6 +45,10 @@ def main():
     ap.add_argument("--config", default="c2_8b_down_prefill")
     ap.add_argument("--sets", type=int, default=8, help="distinct buffer sets the batches rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-two-stream", action="store_true", help="skip the two-stream graph of the steps (an extra figure)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="default workload only: skip the short runs of the decode and 70B workloads whose figures are "
+                         "added to the result line under other_workloads")
     ap.add_argument("--no-machine-probe", action="store_true",
                     help="skip the measurement of the copy rate the machine sustains (1 GiB device copy)")
     ap.add_argument("--eager", action="store_true", help="time eager launches only (no HIP graph capture)")
@@ -323,7 +327,7 @@ def main():
     # is measured in a child process of its own (same inputs, same kernels), so that nothing that happens to a capture
     # over several streams can cost this run its result line.  Prefill workloads only.
     two_stream_us = None
-    if not args.eager and T > 128:
+    if not args.eager and T > 128 and not args.no_two_stream:
         import subprocess
         cmd = [sys.executable, os.path.abspath(__file__), "--two-stream-child", "--config", args.config, "--steps",
                str(args.steps), "--warmup", str(args.warmup), "--sets", str(nsets)]
@@ -481,6 +485,34 @@ def main():
                 np.linalg.norm(y_dev - oracle.linear.mxfp4_gemm(a_dev, as_rm[:Ts].cpu().numpy(), bc_h, bs_h))
                 / np.linalg.norm(y_ref)),
             "note": "bf16 output rounding (2^-9) bounds the second figure" if cfg["out"] == "bf16" else ""}
+    # ---- the other workloads of the metric, in short: child runs of this script (one process per workload keeps their
+    # buffers apart), their main figures under one key.  Only the default run of the headline workload does this.
+    if headline and not (args.no_other_workloads or args.eager or args.smoothing or args.zero_operands):
+        import subprocess
+        others = {}
+        for cfg_name, extra in (("c3_decode_gateup_T1", []), ("c3_decode_down_T16", []),
+                                ("c4_70b_down_prefill", ["--sets", "2", "--steps", "50", "--no-two-stream"]),
+                                ("c5_8b_layer_set_T8192", ["--steps", "20", "--no-two-stream"])):
+            cmd = [sys.executable, os.path.abspath(__file__), "--config", cfg_name, "--no-cpu-baseline",
+                   "--no-machine-probe"] + extra
+            try:
+                child = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=300)
+                if child.returncode != 0:
+                    others[cfg_name] = {"error": f"exit status {child.returncode}"}
+                    continue
+                r = json.loads(child.stdout.strip().splitlines()[-1])
+                c = r["components"]
+                others[cfg_name] = {
+                    "us_per_step": round(r["ms_per_step"] * 1e3, 2), "steps": r["steps"], "buffer_sets": r["config"]["buffer_sets"],
+                    "rotate_quantize_us": c["rotate_quantize"]["us"], "rotate_quantize_frac_hbm_peak": c["rotate_quantize"]["frac_hbm_peak"],
+                    "mxfp4_gemm_us": c["mxfp4_gemm"]["us"], "mxfp4_gemm_frac_mfma_peak": c["mxfp4_gemm"]["frac_mfma_peak"],
+                    "weight_stream_GB/s": c["mxfp4_gemm"]["weight_stream_GB/s"],
+                    "rotq_gemm_fused_call_us": c["rotq_gemm_fused_call"]["us"],
+                    "rotq_gemm_one_kernel_us": c.get("rotq_gemm_one_kernel", {}).get("us"),
+                    "roofline": {k: r["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac")}}
+            except Exception as exc:
+                others[cfg_name] = {"error": str(exc)}
+        result["other_workloads"] = others
     print(json.dumps(result))
 
 
