@@ -241,8 +241,9 @@ int duqpp_rotq_gemm_tiled_packed(const void* x_bf16, int64_t ldx, const void* R_
  * and quantiser as duqpp_rotate_quantize_tiled, hence the same codes bit for bit; the product is that of
  * duqpp_mxfp4_gemm_tiled on those codes up to the order of the fp32 additions.
  * Each of the N / 32 workgroups repeats the rotation of the whole token tile, so this form is slower than the two
- * launches of duqpp_rotq_gemm_tiled at every benchmark shape (measured figures in the design doc) and the library never
- * picks it by itself: it is here so that the one-kernel form can be checked and measured.
+ * launches of duqpp_rotq_gemm_tiled at every benchmark shape (LLaMA-3-8B decode, 1 to 16 tokens: 27-52 us against
+ * 10-11 us on one MI355X) and the library never picks it by itself: it is here so that the one-kernel form can be
+ * checked and measured.
  *   T                    1 .. 32
  *   R_packed             from duqpp_pack_rotation; n_rblocks == K/32, or 1 for a shared block
  *   a_codes_t_dbg, a_scales_t_dbg   nullable (both or neither): receive the activation operand the product was formed

@@ -165,7 +165,10 @@ def test_rotate_quantize_tiled_shared_block(env):
 
 # Shapes with several token tiles per wave and more workgroups than CUs: short rows (an XCD's workgroups take
 # consecutive column chunks), long rows (an XCD owns column chunks), a ragged last token tile, groups that need padding.
-RQ_LARGE_SHAPES = [(2048, 4096, 0), (4100, 2336, 0), (1000, 14368, 0), (2048, 14336, 0), (2048, 4096, 1), (1000, 14368, 1)]
+# The last five make the launch plan pick 5, 6 and 7 waves per workgroup, with and without a spare wave in the last column chunk,
+# and 2 waves per workgroup.
+RQ_LARGE_SHAPES = [(2048, 4096, 0), (4100, 2336, 0), (1000, 14368, 0), (2048, 14336, 0), (2048, 4096, 1), (1000, 14368, 1),
+                   (1000, 4160, 0), (1000, 4928, 1), (1000, 5408, 0), (1000, 6176, 0), (1000, 1280, 0)]
 
 
 @pytest.mark.parametrize("T,K,shared", RQ_LARGE_SHAPES)

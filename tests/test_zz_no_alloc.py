@@ -66,3 +66,33 @@ def test_noalloc_entry_point_rejects_what_does_not_fit_and_bad_arguments():
     assert st == -4
     torch.cuda.synchronize()
     assert bool((y == 7.0).all()) and bool((y2 == 7.0).all())
+
+
+def test_noalloc_entry_point_under_graph_capture():
+    """The callers it is for: a stream capture, where nothing may be allocated.  The per-device set-up is done ahead of
+    the capture (duqpp_init); the captured call is replayed several times with the program's own eager work and
+    synchronisations between the replays, each replay against the eager result of the workspace form."""
+    import torch
+
+    import paper_2604_17789_amd as duqpp
+    duqpp.init()
+    T, K, N = 24, 2048, 300
+    x, R, bct, bst = _case(torch, duqpp, "noalloc-graph-0", T, K, N)
+    y = torch.zeros((T, N), dtype=torch.float32, device=x.device)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            duqpp.rotq_gemm_tiled_noalloc(x, R, bct, bst, N, out=y)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        xn, _, _, _ = _case(torch, duqpp, f"noalloc-graph-{rep + 1}", T, K, N)
+        x.copy_(xn)
+        y.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        want = duqpp.rotq_gemm_tiled(x, R, bct, bst, N)          # eager, with a workspace of its own
+        torch.cuda.synchronize()
+        assert torch.equal(y, want), rep
+        assert float(want.abs().max()) > 0
