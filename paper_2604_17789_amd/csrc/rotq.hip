@@ -334,9 +334,12 @@ __global__ __launch_bounds__(512) void rotq_wave_kernel(RotqParams p) {
     const int jt0 = pair * 2, jt1 = jt0 + 1;                 // < GP (GP is even)
     const int j0 = jt0 < p.G ? jt0 : p.G - 1, j1 = jt1 < p.G ? jt1 : p.G - 1;
 
-    // token tiles are dealt to the ngroups runs as evenly as integers allow
-    const int tile0 = (int)((int64_t)tg * p.ntiles / p.ngroups);
-    const int tile1 = (int)((int64_t)(tg + 1) * p.ntiles / p.ngroups);
+    // Token tiles are dealt to the ngroups runs in turn: run tg takes tiles tg, tg + ngroups, ...  At any moment the
+    // runs of a column chunk are then at neighbouring token tiles, i.e. the chip reads a band of adjacent rows rather
+    // than ngroups bands far apart (measured against contiguous runs: 16.1 -> 15.8 us at 2048 x 14336, 58.9 -> 57.5 us
+    // at 4096 x 28672, 17.3 -> 17.1 us at 8192 x 4096).
+    const int nmine = (p.ntiles - tg + p.ngroups - 1) / p.ngroups;
+    const int ts = p.ngroups;
     const uint32_t ring = lds_offset(lds) + wave * (STAGES * kWaveTileBytes);
 
     // A stage is refilled as soon as its tile has been read into registers, so the ring holds exactly
@@ -344,7 +347,7 @@ __global__ __launch_bounds__(512) void rotq_wave_kernel(RotqParams p) {
     constexpr int P = STAGES;
 #pragma unroll
     for (int d = 0; d < P; ++d)
-        if (tile0 + d < tile1) issue_wave_tile(p, ring + d * kWaveTileBytes, tile0 + d, pair, lane);
+        if (d < nmine) issue_wave_tile(p, ring + d * kWaveTileBytes, tg + d * ts, pair, lane);
     // the rotation blocks arrive behind the first tiles instead of ahead of them
     RotOperand op0, op1;
     if constexpr (PACKED) {
@@ -357,11 +360,12 @@ __global__ __launch_bounds__(512) void rotq_wave_kernel(RotqParams p) {
     }
 
     int stage = 0;
-    for (int tile = tile0; tile < tile1; ++tile) {
+    for (int it = 0; it < nmine; ++it) {
+        const int tile = tg + it * ts;
         // This tile's four transfers have landed once at most the transfers issued after them (up to P - 1
         // tiles) are outstanding: transfers complete in issue order.  Stores complete in no fixed order
         // relative to them, so they are not counted; one that is still outstanding only makes the wait stricter.
-        const int ahead = tile1 - 1 - tile;
+        const int ahead = nmine - 1 - it;
         wait_vmcnt_at_most<4 * (P - 1)>(4 * (ahead < P - 1 ? ahead : P - 1));
         const uint32_t in = ring + stage * kWaveTileBytes + c * 128;
         u32x4 x0[2], x1[2];
@@ -369,7 +373,7 @@ __global__ __launch_bounds__(512) void rotq_wave_kernel(RotqParams p) {
                        in + (((4 + h) ^ (c & 7)) << 4), in + (((6 + h) ^ (c & 7)) << 4),
                        x0[0], x0[1], x1[0], x1[1]);
         // this stage is free again (the reads above have returned): refill it P tiles ahead
-        if (ahead >= P) issue_wave_tile(p, ring + stage * kWaveTileBytes, tile + P, pair, lane);
+        if (ahead >= P) issue_wave_tile(p, ring + stage * kWaveTileBytes, tile + P * ts, pair, lane);
 
         f32x16 acc0 = rotate_tile(op0, x0);
         f32x16 acc1 = rotate_tile(op1, x1);

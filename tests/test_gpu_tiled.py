@@ -474,3 +474,28 @@ def test_two_stream_graph_matches_eager_launches(env):
     p = subprocess.run([sys.executable, os.path.join(here, "two_stream_graph_check.py")], stdout=subprocess.PIPE,
                        stderr=subprocess.STDOUT, text=True, timeout=300)
     assert p.returncode == 0 and "two-stream graph: OK" in p.stdout, p.stdout[-2000:]
+
+
+def test_fused_tiled_call_checks_both_stages_before_launching(env):
+    """A bad argument of the second stage (the product) must be refused before the first stage (rotate+quantise) has
+    been enqueued: the workspace, which rotate+quantise would overwrite, keeps its contents."""
+    torch, duqpp = env
+    T, K, N = 40, 256, 64
+    x = to_dev_bf16(wl.make_activations("fused-args", T, K), torch)
+    R = to_dev(wl.make_rotation_blocks("fused-args", K // 32), torch)
+    bct, bst = duqpp.quantize_weights_tiled(to_dev_bf16(wl.make_weights("fused-args", N, K, 0.02), torch), R)
+    cb, sb = duqpp.tiled_bytes(T, K)
+    ws = torch.full((((cb + 255) // 256 + (sb + 255) // 256) * 256,), 0x5A, dtype=torch.uint8, device=x.device)
+    y = torch.full((T, N), 7.0, dtype=torch.float32, device=x.device)
+    L = duqpp.lib
+    def call(out_dtype=0, ldy=N, yptr=None):
+        return L.duqpp_rotq_gemm_tiled(x.data_ptr(), K, R.data_ptr(), K // 32, bct.data_ptr(), bst.data_ptr(), T, N, K,
+                                       y.data_ptr() if yptr is None else yptr, out_dtype, ldy, ws.data_ptr(), ws.numel(), None)
+    assert call(out_dtype=9) == -4
+    assert call(ldy=N - 1) == -2
+    assert call(yptr=y.data_ptr() + 2) == -3
+    torch.cuda.synchronize()
+    assert bool((ws == 0x5A).all()) and bool((y == 7.0).all())
+    assert call() == 0
+    torch.cuda.synchronize()
+    assert not bool((ws == 0x5A).all()) and torch.equal(y, duqpp.rotq_gemm_tiled(x, R, bct, bst, N))
