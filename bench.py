@@ -45,6 +45,9 @@ def main():
     ap.add_argument("--config", default="c2_8b_down_prefill")
     ap.add_argument("--sets", type=int, default=8, help="distinct buffer sets the batches rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--one-kernel", action="store_true",
+                    help="time the one-kernel form (duqpp_rotq_gemm_fused_decode) also at more than 32 tokens, where it "
+                         "takes milliseconds per step: use with a small --steps")
     ap.add_argument("--no-two-stream", action="store_true", help="skip the two-stream graph of the steps (an extra figure)")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="default workload only: skip the short runs of the decode and 70B workloads whose figures are "
@@ -319,7 +322,7 @@ def main():
     fused = time_region(fused_step, eager_only=args.eager)
     # up to 32 tokens: the one-kernel form (rotation and quantiser in the prologue of every product workgroup)
     one_kernel = None
-    if T <= 32:
+    if T <= 32 or args.one_kernel:
         one_kernel = time_region(lambda s: [duqpp.rotq_gemm_fused_decode(l["x"], l["Rp"], l["bc"], l["bs"], l["N"],
                                                                          out_dtype=out_dtype, out=l["y"]) for l in s],
                                  eager_only=args.eager)

@@ -235,16 +235,17 @@ int duqpp_rotq_gemm_tiled_packed(const void* x_bf16, int64_t ldx, const void* R_
                                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * The online path of Eq. 5 as ONE kernel, for up to 32 tokens: every workgroup rotates (Eq. 4) and quantises (Eq. 2)
- * the activations it needs in the prologue of its K steps and multiplies them with its 32 output channels of the
- * tiled weights; no activation operand exists in memory and no workspace is needed.  Same device code for rotation
+ * The online path of Eq. 5 as ONE kernel, shaped for up to 32 tokens: every workgroup rotates (Eq. 4) and quantises
+ * (Eq. 2) the activations it needs in the prologue of its K steps and multiplies them with its 32 output channels of
+ * the tiled weights; no activation operand exists in memory and no workspace is needed.  More than 32 tokens run as
+ * independent tiles of 32 tokens, each streaming the weights again.  Same device code for rotation
  * and quantiser as duqpp_rotate_quantize_tiled, hence the same codes bit for bit; the product is that of
  * duqpp_mxfp4_gemm_tiled on those codes up to the order of the fp32 additions.
  * Each of the N / 32 workgroups repeats the rotation of the whole token tile, so this form is slower than the two
  * launches of duqpp_rotq_gemm_tiled at every benchmark shape (LLaMA-3-8B decode, 1 to 16 tokens: 27-52 us against
- * 10-11 us on one MI355X) and the library never picks it by itself: it is here so that the one-kernel form can be
+ * 10-11 us on one MI355X; prefill shapes: tens of milliseconds against tenths) and the library never picks it by itself: it is here so that the one-kernel form can be
  * checked and measured.
- *   T                    1 .. 32
+ *   T                    1 .. 32 * 65535
  *   R_packed             from duqpp_pack_rotation; n_rblocks == K/32, or 1 for a shared block
  *   a_codes_t_dbg, a_scales_t_dbg   nullable (both or neither): receive the activation operand the product was formed
  *                        from, in the tiled layout for T rows (duqpp_tiled_bytes(T, K)), 256-byte aligned

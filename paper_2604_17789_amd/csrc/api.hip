@@ -420,7 +420,7 @@ int duqpp_rotq_gemm_fused_decode(const void* x_bf16, int64_t ldx, const void* R_
     if ((a_codes_t_dbg == nullptr) != (a_scales_t_dbg == nullptr)) return DUQPP_ERR_NULL;
     int st = validate_rows_K(T, K, ldx, n_rblocks);
     if (st != DUQPP_OK) return st;
-    if (T > 32 || N < 1 || N > (int64_t)1 << 30 || ldy < N) return DUQPP_ERR_SHAPE;
+    if (T > kFusedMaxT || N < 1 || N > (int64_t)1 << 30 || ldy < N) return DUQPP_ERR_SHAPE;
     if (out_dtype != DUQPP_F32 && out_dtype != DUQPP_BF16) return DUQPP_ERR_DTYPE;
     if (!aligned_to(x_bf16, 16) || (ldx % 8) != 0 || !aligned_to(R_packed, 16) || !aligned_to(b_codes_t, 256) ||
         !aligned_to(b_scales_t, 256) || !aligned_to(y, out_dtype == DUQPP_F32 ? 4 : 2) ||

@@ -166,8 +166,9 @@ struct FusedDecodeParams {
     const uint8_t* b_codes; const uint8_t* b_scales;      // tiled weights
     int N, G, GP;
     void* y; int64_t ldy; int out_bf16;
-    uint8_t* dbg_codes; uint8_t* dbg_scales;              // nullable: the activation operand (tiled, one row tile)
+    uint8_t* dbg_codes; uint8_t* dbg_scales;              // nullable: the activation operand (tiled, T rows)
 };
+constexpr int kFusedMaxT = 32 * 65535;                    // token tiles run along blockIdx.y
 hipError_t launch_rotq_gemm_fused_decode(const FusedDecodeParams& p, hipStream_t stream);
 
 constexpr int kDecodeMaxT = 128;   // up to four activation row tiles go to the weight-streaming kernel

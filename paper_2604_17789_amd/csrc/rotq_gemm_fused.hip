@@ -1,5 +1,6 @@
-// One-kernel form of the online path for up to 32 tokens: rotate (Eq. 4 / Eq. 5), quantise (Eq. 2) and multiply
-// (Eq. 5) in a single launch, with no activation operand in memory between the stages.
+// One-kernel form of the online path, shaped for up to 32 tokens: rotate (Eq. 4 / Eq. 5), quantise (Eq. 2) and
+// multiply (Eq. 5) in a single launch, with no activation operand in memory between the stages.  More tokens run as
+// independent tiles of 32 along blockIdx.y, each streaming the weights again.
 //
 // Shape.  As the weight-streaming kernel (gemm_decode.hip): one workgroup of 8 waves per 32 output channels, the
 // waves split K into contiguous runs of 256-wide steps, each accumulates one 32 x 32 tile, and the eight partial
@@ -41,6 +42,7 @@ __global__ __launch_bounds__(kFusedWaves * 64) void rotq_gemm_fused_decode_kerne
     const int wave = threadIdx.x >> 6;
     const int t = lane & 31, g = lane >> 5;                // token (activation side) or channel (weight side), half
     const int rt = blockIdx.x;                             // weight row tile
+    const int mt = blockIdx.y;                             // token tile
     const int NI = p.GP / 8;
     const int per = (NI + kFusedWaves - 1) / kFusedWaves;
     const int s0 = wave * per;
@@ -51,8 +53,8 @@ __global__ __launch_bounds__(kFusedWaves * 64) void rotq_gemm_fused_decode_kerne
     const uint8_t* b_scales = p.b_scales + (int64_t)rt * NI * 256 + lane * 4;
     // lanes without a token of their own rotate token 0 again (same cache lines); their operand is then replaced by
     // the padding of the tiled layout (code 0, scale 127), exactly what the separate launch writes for such rows
-    const bool own = t < p.T;
-    const uint16_t* xrow = p.x + (int64_t)(own ? t : 0) * p.ldx + 8 * g;
+    const bool own = 32 * mt + t < p.T;
+    const uint16_t* xrow = p.x + (int64_t)(own ? 32 * mt + t : 0) * p.ldx + 8 * g;
     const uint8_t* rp = p.r_packed;
     const bool shared_r = p.r_stride == 0;
     RotOperand opS;
@@ -100,11 +102,11 @@ __global__ __launch_bounds__(kFusedWaves * 64) void rotq_gemm_fused_decode_kerne
             sa |= (g ? byteB : byteA) << (8 * i);
         }
         if (p.dbg_codes && blockIdx.x == 0) {
-            // the activation operand as the separate launch would have written it (one row tile: T <= 32)
+            // the activation operand as the separate launch would have written it
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                *(u32x4*)(p.dbg_codes + ((int64_t)(8 * s + 4 * g + i) * 32 + t) * 16) = a[i];
-            *(uint32_t*)(p.dbg_scales + (((int64_t)s * 2 + g) * 32 + t) * 4) = sa;
+                *(u32x4*)(p.dbg_codes + (((int64_t)mt * p.GP + 8 * s + 4 * g + i) * 32 + t) * 16) = a[i];
+            *(uint32_t*)(p.dbg_scales + ((((int64_t)mt * NI + s) * 2 + g) * 32 + t) * 4) = sa;
         }
         acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fp4_operand(a[0]), fp4_operand(b[0]), acc, 4, 4, 0, (int)sa, 0, (int)sb);
         acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fp4_operand(a[1]), fp4_operand(b[1]), acc, 4, 4, 1, (int)sa, 1, (int)sb);
@@ -123,7 +125,7 @@ __global__ __launch_bounds__(kFusedWaves * 64) void rotq_gemm_fused_decode_kerne
         float sum = 0.f;
 #pragma unroll
         for (int w = 0; w < kFusedWaves; ++w) sum += part[w][e][lane];
-        const int tok = 8 * (e / 4) + 4 * g + (e % 4);
+        const int tok = 32 * mt + 8 * (e / 4) + 4 * g + (e % 4);
         const int col = rt * 32 + t;
         if (tok < p.T && col < p.N) {
             if (OUT_BF16) ((uint16_t*)p.y)[(int64_t)tok * p.ldy + col] = f32_to_bf16_rne(sum);
@@ -133,8 +135,8 @@ __global__ __launch_bounds__(kFusedWaves * 64) void rotq_gemm_fused_decode_kerne
 }
 
 hipError_t launch_rotq_gemm_fused_decode(const FusedDecodeParams& p, hipStream_t stream) {
-    if (p.T < 1 || p.T > 32) return hipErrorInvalidValue;
-    dim3 grid((unsigned)((p.N + 31) / 32)), block(kFusedWaves * 64);
+    if (p.T < 1 || p.T > kFusedMaxT) return hipErrorInvalidValue;
+    dim3 grid((unsigned)((p.N + 31) / 32), (unsigned)((p.T + 31) / 32)), block(kFusedWaves * 64);
     return p.out_bf16 ? launch(rotq_gemm_fused_decode_kernel<true>, grid, block, 0, stream, p)
                       : launch(rotq_gemm_fused_decode_kernel<false>, grid, block, 0, stream, p);
 }

@@ -1,4 +1,5 @@
-"""GPU parity of the one-kernel form of the online path (duqpp_rotq_gemm_fused_decode, up to 32 tokens): the
+"""GPU parity of the one-kernel form of the online path (duqpp_rotq_gemm_fused_decode; shaped for up to 32 tokens,
+more run as tiles of 32): the
 activation codes and scales it forms in its prologue must be the bytes duqpp_rotate_quantize_tiled writes (which the
 other GPU tests hold to the oracle), and its product must match the oracle's product of those codes."""
 import numpy as np
@@ -28,6 +29,8 @@ SHAPES = [
     (32, 96, 32, 0),          # a single group: seven of the eight waves have no step
     (7, 300, 2048, 1),        # the shared block of Sec. 4.2
     (20, 8200, 544, 0),       # 257 weight row tiles
+    (100, 200, 1184, 0),      # four token tiles, the last with four tokens
+    (300, 264, 2048, 1),      # ten token tiles, shared block
 ]
 
 
@@ -56,7 +59,7 @@ def test_one_kernel_form_against_the_two_launches_and_the_oracle(env, T, N, K, s
     assert np.all(np.abs(yh - ref) <= 1e-5 * per_element_gemm_bound(ac, asc, bc, bsc, mxfp4.dequantize))
     np.testing.assert_array_equal(bf16_dev_to_bits(y16), linear.round_to_bf16_bits(yh))
     assert rel_fro(yh, y_two.cpu().numpy()) <= 1e-6            # same codes, another order of the fp32 additions
-    if N >= 8192 and T > 16:
+    if N >= 8192 and 16 < T <= 32:
         # here the two-launch path runs the weight-streaming kernel with whole row tiles, whose K split and reduction
         # this kernel shares: the same additions in the same order
         assert torch.equal(y, y_two)
@@ -70,8 +73,9 @@ def test_one_kernel_form_checks_its_arguments(env):
     bct, bst = duqpp.quantize_weights_tiled(torch.zeros((40, 64), dtype=torch.bfloat16, device="cuda:0"), R)
     y = torch.full((33, 40), 7.0, dtype=torch.float32, device="cuda:0")
     L = duqpp.lib
-    args = lambda T, dt=0, rp=Rp.data_ptr(): (x.data_ptr(), 64, rp, 2, bct.data_ptr(), bst.data_ptr(), T, 40, 64, y.data_ptr(), dt, 40, None, None, None)
-    assert L.duqpp_rotq_gemm_fused_decode(*args(33)) == -2           # more than one token tile
+    args = lambda T, dt=0, rp=Rp.data_ptr(), nb=2: (x.data_ptr(), 64, rp, nb, bct.data_ptr(), bst.data_ptr(), T, 40, 64, y.data_ptr(), dt, 40, None, None, None)
+    assert L.duqpp_rotq_gemm_fused_decode(*args(8, 0, Rp.data_ptr(), 3)) == -2    # three blocks for two groups
+    assert L.duqpp_rotq_gemm_fused_decode(*args(0)) == -2
     assert L.duqpp_rotq_gemm_fused_decode(*args(8, 3)) == -4
     assert L.duqpp_rotq_gemm_fused_decode(*args(8, 0, None)) == -1
     assert L.duqpp_rotq_gemm_fused_decode(*args(8, 0, Rp.data_ptr() + 8)) == -3
