@@ -217,3 +217,50 @@ def test_quantiser_stage_every_value_near_every_threshold(env):
     z = np.zeros((64, 64), dtype=np.float32)
     z[::2] = -0.0
     _dbg_check(env, z)
+
+
+def test_groups_are_independent_on_the_device(env):
+    """Sec. 4.2: every group of 32 has its own scale, so changing one block of the input changes the codes and the
+    scale of that group only (for the tokens changed) -- checked on the device's output byte for byte."""
+    torch, duqpp = env
+    T, K = 96, 2048
+    G = K // 32
+    xb = wl.make_activations("gpu-rq-indep", T, K, (wl.OutlierSpec(8, 50.0),))
+    R = to_dev(wl.make_rotation_blocks("gpu-rq-indep", G), torch)
+    c0, s0 = duqpp.rotate_quantize(to_dev_bf16(xb, torch), R)
+    xb2 = xb.copy()
+    j, toks = 37, np.array([0, 31, 32, 95])
+    xb2[toks[:, None], 32 * j + np.arange(32)[None, :]] = wl.f32_to_bf16_bits(
+        1000.0 * wl.bf16_bits_to_f32(xb[toks[:, None], 32 * j + np.arange(32)[None, :]]) + 3.0)
+    c1, s1 = duqpp.rotate_quantize(to_dev_bf16(xb2, torch), R)
+    torch.cuda.synchronize()
+    c0, s0, c1, s1 = (t.cpu().numpy() for t in (c0, s0, c1, s1))
+    same_c = (c0.reshape(T, G, 16) == c1.reshape(T, G, 16)).all(axis=-1)
+    same_s = s0 == s1
+    touched = np.zeros((T, G), dtype=bool)
+    touched[toks, j] = True
+    assert same_c[~touched].all() and same_s[~touched].all()
+    assert not same_s[touched].any()                     # a thousandfold input moves every touched group's scale
+
+
+def test_representable_inputs_survive_the_device_quantiser(env):
+    """dequant(quant(x)) = x for values that are E2M1 values times a power of two with the group's largest magnitude
+    4 or 6 (so that the scale is that power of two), and quantising the decoded values again gives the same bytes."""
+    torch, duqpp = env
+    rng = np.random.default_rng(11)
+    mags = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
+    rows, K = 256, 256
+    v = mags[rng.integers(0, 8, size=(rows, K))] * rng.choice([-1.0, 1.0], size=(rows, K))
+    v.reshape(rows, K // 32, 32)[:, :, 5] = rng.choice([4.0, 6.0, -4.0, -6.0], size=(rows, K // 32))
+    e = rng.integers(-100, 100, size=(rows, K // 32))
+    y = np.ldexp(v, np.repeat(e, 32, axis=1)).astype(np.float32)
+    codes, scales = duqpp.quantize_f32_dbg(to_dev(y, torch))
+    torch.cuda.synchronize()
+    codes, scales = codes.cpu().numpy(), scales.cpu().numpy()
+    np.testing.assert_array_equal(scales, (e + 127).astype(np.uint8))
+    back = mxfp4.dequantize(codes, scales)
+    np.testing.assert_array_equal(back, y.astype(np.float64))
+    c2, s2 = duqpp.quantize_f32_dbg(to_dev(back.astype(np.float32), torch))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(c2.cpu().numpy(), codes)
+    np.testing.assert_array_equal(s2.cpu().numpy(), scales)
