@@ -27,7 +27,7 @@ FP4_PEAK_TFLOPS = 10100.0     # MI355X dense MXFP4 matrix peak, published (256 C
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE (x 2.000) + WRITE_SIZE (x 1.000), the factors a plain
 # 256 MiB device copy gives for the same counters; workload c2_8b_down_prefill.  Counter runs are separate runs of
 # this script under the profiler: the figures are copied from their summary, not measured by the run that prints them.
-MEASURED_TRAFFIC = {"gemm": 125.12e6 + 16.78e6, "rotq": 61.56e6 + 15.60e6}
+MEASURED_TRAFFIC = {"gemm": 125.12e6 + 16.78e6, "rotq": 61.54e6 + 15.60e6}
 TRAFFIC_SOURCE = ("profiles/gemm_tiled_and_rotq_c2_8b_down_prefill_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE and "
                   "WRITE_SIZE runs of this workload, scaled by a plain copy's readings); not measured in this run")
 
