@@ -3,7 +3,7 @@ power-of-two scale; each value is stored as a 4-bit E2M1 code.
 
 Readings taken where Eq. 2 is silent or garbled (listed in the design notes):
   * the exponent offset b is the E2M1 maximum exponent, 2: s = 2^(floor(log2 amax) - 2);
-  * "nearest representable value" = one round-to-nearest on the E2M1 grid with ties
+  * rounding to the nearest value of the format = one round-to-nearest on the E2M1 grid with ties
     to the code whose mantissa bit is 0, then saturation at +-6;
   * groups run along the last (reduction) axis;
   * an all-zero group gets scale byte 0; the exponent is clamped to [-127, 127];
