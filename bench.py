@@ -214,26 +214,36 @@ def main():
     # device synchronisation.  The figure comes from a HIP graph of exactly those launches (the kernels record no memset
     # nodes): issued one by one from Python, launches of a 3-10 us kernel measure the interpreter, and a graph is never
     # bound by the host.  The figure of eager launches is kept beside it.
-    # The chip's clock follows its power draw: the first few dozen launches after an idle stretch run 10-15 % faster
-    # than the sustained rate, and any single reading moves by several per cent with what ran before it.  Every timed
-    # region is therefore preceded, without a pause, by at least kSustain untimed runs of the same work (more if
-    # --warmup asks for more), and the graph is replayed kReps + 1 times back to back, each replay of exactly args.steps
-    # steps between its own pair of events; the figure is the median of the last kReps.  The host enqueues all replays
-    # while the GPU is busy with the first, so none of them contains the host's latency of launching a graph (some
-    # 100 us: 5-10 us per step when only 20 steps are timed).
-    kSustain, kReps = 64, 5
+    # The chip's clock follows its power draw.  After an idle stretch (the host-side capture of a graph is one) the
+    # first few dozen launches run faster than the sustained rate and the next 10-30 ms slower than it (at c2, replays
+    # of 20 rotate+quantise launches back to back: 16.3, 16.3, 16.7, 18.0, 18.1, 18.6, 19.7, ... and 16.2 from the 40th
+    # millisecond on), so a short timed region measures where in that transient it happens to sit.  Every timed region
+    # is therefore preceded, without a pause, by untimed runs of the same work: at least kSustain eager runs (more if
+    # --warmup asks for more), and, for a graph, as many untimed replays as fill kLeadMs of GPU time.  Then the graph is
+    # replayed kReps times more, back to back, each replay of exactly args.steps steps between its own pair of events;
+    # the figure is their median.  The host enqueues replays far ahead of the GPU, so none of them contains the host's
+    # latency of launching a graph (some 100 us: 5-10 us per step when only 20 steps are timed).
+    kSustain, kReps, kLeadMs = 64, 5, 40.0
     n_warm = max(args.warmup, kSustain)
 
     def time_replay(g):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        lead = int(min(2000, max(1, kLeadMs / max(e0.elapsed_time(e1), 1e-3))))
+        for _ in range(lead):
+            g.replay()
         marks = []
-        for _ in range(kReps + 1):
+        for _ in range(kReps):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             g.replay()
             e1.record()
             marks.append((e0, e1))
         torch.cuda.synchronize()
-        return sorted(a.elapsed_time(b) for a, b in marks[1:])[kReps // 2] * 1e3 / args.steps
+        return sorted(a.elapsed_time(b) for a, b in marks)[kReps // 2] * 1e3 / args.steps
 
     def time_region(fn, eager_only=False):
         for i in range(n_warm):
@@ -378,7 +388,7 @@ def main():
         "ms_per_step_graph_replay_host_clock": round(whole["wall_us"] * 1e-3, 5),
         "ms_per_step_two_stream_graph": None if two_stream_us is None else round(two_stream_us * 1e-3, 5),
         "launch": ("HIP graph replay of the timed steps on one stream, timed by events on that stream (median of "
-                   f"{kReps} back-to-back replays after {n_warm} untimed steps)"
+                   f"{kReps} back-to-back replays that follow {n_warm} untimed steps and {kLeadMs:.0f} ms of untimed replays)"
                    if whole["graph"] else "eager launches on one stream, timed by events on that stream"),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "mxfp4 (E2M1 codes + E8M0 scales; fp32 rotation and accumulation)",
