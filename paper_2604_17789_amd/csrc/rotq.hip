@@ -318,12 +318,13 @@ __global__ __launch_bounds__(512) void rotq_wave_kernel(RotqParams p) {
     int logical;
     logical_workgroup(logical);
     // Which workgroups share an XCD (the renumbering keeps consecutive logical ones together):
-    //  - by_columns: an XCD owns a few column chunks for all token runs, so each rotation block is fetched
-    //    into one L2 only.  Its workgroups sit at a few fixed offsets within every row of X, and a row length
-    //    that is a multiple of the L2 channel interleave sends them all to the same channels -- harmless
-    //    only when an XCD owns enough chunks (>= 3 KiB of a row) to spread over the channels;
-    //  - otherwise consecutive workgroups take consecutive chunks of the same token rows: together they
-    //    read whole rows, every channel is used, and every XCD fetches every rotation block.
+    //  - by_columns: an XCD owns a few column chunks for all token runs, so each rotation block is fetched into one
+    //    L2 only, and (token tiles being dealt to the runs in turn, below) its workgroups read neighbouring rows of
+    //    those columns at any moment;
+    //  - otherwise consecutive workgroups take consecutive chunks of the same token rows: together they read whole
+    //    rows and every XCD fetches every rotation block.  Kept for rows shorter than 4 KiB, where it measures a few
+    //    per cent faster; from 4 KiB on owning columns wins or ties at every shape tried (up to 19 %, most with few
+    //    hundred tokens).
     const int chunk = p.by_columns ? logical / p.ngroups : logical % p.nchunks;
     const int tg = p.by_columns ? logical % p.ngroups : logical / p.nchunks;
     const int lane = threadIdx.x & 63;
@@ -433,7 +434,7 @@ void plan_rotq(RotqParams& p) {
             }
         }
         p.nchunks = (npairs + p.waves - 1) / p.waves;
-        p.by_columns = p.nchunks >= 3 * kNumXCD;
+        p.by_columns = p.G >= 64;                           // rows of 4 KiB or more (K >= 2048)
     } else {
         p.waves = kRotqWaves;
         p.nchunks = (p.G + kBlocksPerWG - 1) / kBlocksPerWG;
