@@ -79,9 +79,10 @@ struct RotqParams {
     int nchunks;         // column chunks (each covers waves*2 blocks)
     int waves;           // wavefronts per workgroup
     int by_columns;      // tiled-output kernel: an XCD owns column chunks (1) or token runs (0)
+    int stages;          // tiled-output kernel: depth of a wave's ring of token tiles (2 or 3)
 };
 hipError_t launch_rotq(const RotqParams& p, hipStream_t stream);
-void plan_rotq(RotqParams& p);    // fills ntiles / tiles_per_wg / ngroups / nchunks / waves / by_columns
+void plan_rotq(RotqParams& p);    // fills ntiles / tiles_per_wg / ngroups / nchunks / waves / by_columns / stages
 
 constexpr int kPackedRotationBlockBytes = 6144;   // three bf16 pieces of a 32 x 32 block
 struct PackRotationParams {

@@ -407,18 +407,34 @@ __global__ __launch_bounds__(512) void rotq_wave_kernel(RotqParams p) {
 
 constexpr int kRotqStages = 4;             // 3 tiles in flight, one in use
 
-constexpr int kWaveStages = 2;             // per-wave ring of the tiled-output kernel: 2 tiles of 4 KiB in flight
-                                           // (deeper rings measured no faster at any of the benchmark shapes)
+constexpr int kWaveStages = 2;             // per-wave ring of the tiled-output kernel: 2 tiles of 4 KiB in flight, or
+constexpr int kWaveStagesDeep = 3;         // 3 where a workgroup has only four waves to keep the CU's requests going
 
 void plan_rotq(RotqParams& p) {
     p.ntiles = (p.rows + 31) / 32;
+    p.stages = kWaveStages;
+    bool one_per_cu = true;                                 // one workgroup resident per CU, or 8 / waves of them
     if (p.tiled) {
         // wave-private pipelines: a workgroup is `waves` independent waves on adjacent block pairs.
         // Fewer waves per workgroup when the problem is too small to give every CU a full one.
         const int npairs = p.GP / 2;
         p.waves = 8;
         while (p.waves > 1 && (int64_t)((npairs + p.waves - 1) / p.waves) * p.ntiles < kNumCU) p.waves /= 2;
-        if (p.waves == 8) {
+        one_per_cu = p.waves >= 5;
+        if (p.waves == 8 && npairs % 8 == 0) {
+            // Enough work for every CU, and rows that eight-wave workgroups would cut into 1 KiB chunks at 1 KiB
+            // boundaries (K a multiple of 512: 4096, 8192, ...).  With such chunks the time depends on where the
+            // buffers happen to lie (8192 x 4096 on two boxes: 17.3 and 20.4 us; 4096 x 8192: 17.6 and 20.7 us);
+            // four waves per workgroup, one workgroup per CU, each wave with twice the tiles and a ring one deeper,
+            // run at the better of those figures on both (17.5, 17.5; 17.6, 17.4) and fetch R half as often.  The
+            // deeper ring pays from 8 tiles per wave on; with fewer, two stages are 3 % faster.
+            p.waves = 4;
+            one_per_cu = true;
+            const int nch = npairs / 4;
+            int groups = kNumCU / nch;
+            groups = groups < 1 ? 1 : (groups > p.ntiles ? p.ntiles : groups);
+            if ((p.ntiles + groups - 1) / groups >= 8) p.stages = kWaveStagesDeep;
+        } else if (p.waves == 8) {
             // Enough work for every CU: 5 to 8 waves per workgroup, whichever leaves the busiest CU the fewest
             // (wave, tile) units in the one resident round; more waves when equal.  K = 14336 has 224 block pairs:
             // 8 waves give 28 column chunks x 8 token runs = 224 workgroups on 256 CUs, 7 waves 32 x 8 = 256.
@@ -441,7 +457,7 @@ void plan_rotq(RotqParams& p) {
     }
     // One resident round: each wave keeps its R blocks in registers and walks as many token
     // tiles as the problem allows, so the fetch and split of R is amortised.
-    const int64_t slots = (int64_t)kNumCU * kRotqWGPerCU * (p.waves >= 5 ? 1 : kRotqWaves / p.waves);
+    const int64_t slots = (int64_t)kNumCU * kRotqWGPerCU * (one_per_cu ? 1 : kRotqWaves / p.waves);
     int groups = (int)(slots / p.nchunks);
     if (groups < 1) groups = 1;
     if (groups > p.ntiles) groups = p.ntiles;
@@ -460,7 +476,12 @@ hipError_t setup_rotq() {
         if (e != hipSuccess) return e;
         e = allow_dynamic_lds((const void*)rotq_wave_kernel<kWaveStages, false>, kWaveLdsMax);
         if (e != hipSuccess) return e;
-        return allow_dynamic_lds((const void*)rotq_wave_kernel<kWaveStages, true>, kWaveLdsMax);
+        e = allow_dynamic_lds((const void*)rotq_wave_kernel<kWaveStages, true>, kWaveLdsMax);
+        if (e != hipSuccess) return e;
+        constexpr int kDeepLdsMax = 8 * kWaveStagesDeep * kWaveTileBytes;
+        e = allow_dynamic_lds((const void*)rotq_wave_kernel<kWaveStagesDeep, false>, kDeepLdsMax);
+        if (e != hipSuccess) return e;
+        return allow_dynamic_lds((const void*)rotq_wave_kernel<kWaveStagesDeep, true>, kDeepLdsMax);
     });
 }
 
@@ -471,9 +492,14 @@ hipError_t launch_rotq(const RotqParams& p, hipStream_t stream) {
     dim3 grid((unsigned)((int64_t)p.nchunks * p.ngroups));
     if (p.tiled) {
         if (p.waves < 1 || p.waves > 8) return hipErrorInvalidValue;
-        const size_t lds = (size_t)p.waves * kWaveStages * kWaveTileBytes;
-        return p.r_packed ? launch(rotq_wave_kernel<kWaveStages, true>, grid, dim3(p.waves * 64), lds, stream, p)
-                          : launch(rotq_wave_kernel<kWaveStages, false>, grid, dim3(p.waves * 64), lds, stream, p);
+        if (p.stages != kWaveStages && p.stages != kWaveStagesDeep) return hipErrorInvalidValue;
+        const size_t lds = (size_t)p.waves * p.stages * kWaveTileBytes;
+        const dim3 block(p.waves * 64);
+        if (p.stages == kWaveStagesDeep)
+            return p.r_packed ? launch(rotq_wave_kernel<kWaveStagesDeep, true>, grid, block, lds, stream, p)
+                              : launch(rotq_wave_kernel<kWaveStagesDeep, false>, grid, block, lds, stream, p);
+        return p.r_packed ? launch(rotq_wave_kernel<kWaveStages, true>, grid, block, lds, stream, p)
+                          : launch(rotq_wave_kernel<kWaveStages, false>, grid, block, lds, stream, p);
     }
     if (p.r_packed) return hipErrorInvalidValue;             // the packed blocks feed the tiled-output kernel only
     return launch(rotq_kernel<kRotqWaves, kRotqStages, false>, grid, dim3(kRotqWaves * 64), TL::kLdsBytes, stream, p);

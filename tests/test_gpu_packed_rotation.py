@@ -58,7 +58,7 @@ def test_packed_bytes_are_the_exact_split_in_operand_order(env, n):
 
 
 SHAPES = [(64, 4096, 0), (1, 4096, 0), (16, 14336, 0), (77, 1184, 0), (33, 32, 0), (300, 2048, 1), (2048, 14336, 0),
-          (1000, 14368, 1), (2048, 4096, 0)]
+          (1000, 14368, 1), (2048, 4096, 0), (4100, 4096, 0), (8192, 2048, 1)]   # the last two: three-stage ring
 
 
 @pytest.mark.parametrize("T,K,shared", SHAPES)
