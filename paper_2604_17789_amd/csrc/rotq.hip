@@ -421,13 +421,15 @@ void plan_rotq(RotqParams& p) {
         p.waves = 8;
         while (p.waves > 1 && (int64_t)((npairs + p.waves - 1) / p.waves) * p.ntiles < kNumCU) p.waves /= 2;
         one_per_cu = p.waves >= 5;
-        if (p.waves == 8 && npairs % 8 == 0) {
-            // Enough work for every CU, and rows that eight-wave workgroups would cut into 1 KiB chunks at 1 KiB
-            // boundaries (K a multiple of 512: 4096, 8192, ...).  With such chunks the time depends on where the
-            // buffers happen to lie (8192 x 4096 on two boxes: 17.3 and 20.4 us; 4096 x 8192: 17.6 and 20.7 us);
-            // four waves per workgroup, one workgroup per CU, each wave with twice the tiles and a ring one deeper,
-            // run at the better of those figures on both (17.5, 17.5; 17.6, 17.4) and fetch R half as often.  The
-            // deeper ring pays from 8 tiles per wave on; with fewer, two stages are 3 % faster.
+        if (p.waves == 8 && (p.G & (p.G - 1)) == 0) {
+            // Enough work for every CU, and a row length that is a power of two (K = 4096, 8192, ...).  With
+            // eight-wave workgroups such rows are cut into 1 KiB chunks that sit at the same offset in every row, and
+            // the time then depends on where the buffers happen to lie (8192 x 4096 on two boxes: 17.3 and 20.4 us;
+            // 4096 x 8192: 17.6 and 20.7 us); four waves per workgroup, one workgroup per CU, each wave with twice
+            // the tiles and a ring one deeper, run at the better of those figures on both (17.5, 17.5; 17.6, 17.4)
+            // and fetch R half as often.  The deeper ring pays from 8 tiles per wave on; with fewer, two stages are
+            // 3 % faster.  Other row lengths (14336, 28672: seven times a power of two) keep the search below, which
+            // measures as fast there or faster.
             p.waves = 4;
             one_per_cu = true;
             const int nch = npairs / 4;

@@ -167,7 +167,7 @@ def test_rotate_quantize_tiled_shared_block(env):
 # consecutive column chunks), long rows (an XCD owns column chunks), a ragged last token tile, groups that need padding.
 # The last five make the launch plan pick 5, 6 and 7 waves per workgroup, with and without a spare wave in the last column chunk,
 # and 2 waves per workgroup.
-# The three after those have rows of whole KiB chunks and enough tokens for the four-wave plan: 4 tiles per wave (two-stage
+# The three after those have rows of a power-of-two length and enough tokens for the four-wave plan: 4 tiles per wave (two-stage
 # ring), then 9 with a ragged last tile and 8 (three-stage ring), the last with a shared block.
 RQ_LARGE_SHAPES = [(2048, 4096, 0), (4100, 2336, 0), (1000, 14368, 0), (2048, 14336, 0), (2048, 4096, 1), (1000, 14368, 1),
                    (1000, 4160, 0), (1000, 4928, 1), (1000, 5408, 0), (1000, 6176, 0), (1000, 1280, 0),
