@@ -43,13 +43,22 @@ def rotq_gemm(x, R, b_codes, b_scales):
     return linear.mxfp4_gemm(a_codes, a_scales, b_codes, b_scales)
 
 
-def per_group_normalised_error(y32, codes, scales):
-    """Fig. 1 statistic: ||Q(x) - x||_2 / ||x||_2 per group of 32, averaged over groups
-    with non-zero norm."""
+def per_group_normalised_errors(y32, codes, scales):
+    """Fig. 1 statistic before its mean: ||Q(x) - x||_2 / ||x||_2 of every group of 32, as an array [rows, K/32];
+    a group without norm has no ratio and reads -1."""
     y = np.asarray(y32, dtype=np.float64)
     d = mxfp4.dequantize(codes, scales) - y
     G = y.shape[1] // 32
     num = np.linalg.norm(d.reshape(y.shape[0], G, 32), axis=-1)
     den = np.linalg.norm(y.reshape(y.shape[0], G, 32), axis=-1)
     ok = den > 0
-    return float(np.mean(num[ok] / den[ok]))
+    out = np.full(den.shape, -1.0)
+    out[ok] = num[ok] / den[ok]
+    return out
+
+
+def per_group_normalised_error(y32, codes, scales):
+    """Fig. 1 statistic: ||Q(x) - x||_2 / ||x||_2 per group of 32, averaged over groups
+    with non-zero norm."""
+    r = per_group_normalised_errors(y32, codes, scales)
+    return float(np.mean(r[r >= 0]))

@@ -67,14 +67,14 @@ MISTAKES = [
     ("weights divided by Lambda instead of multiplied", "pipeline.py",
      [("w = smoothing.apply(w, lam, inverse=False)", "w = smoothing.apply(w, lam, inverse=True)")]),
     ("group error statistic: squared norms (no square root)", "pipeline.py",
-     [("return float(np.mean(num[ok] / den[ok]))", "return float(np.mean((num[ok] / den[ok]) ** 2))")]),
+     [("out[ok] = num[ok] / den[ok]", "out[ok] = (num[ok] / den[ok]) ** 2")]),
     ("group error statistic: normalised by the quantised group instead of the group itself", "pipeline.py",
      [("den = np.linalg.norm(y.reshape(y.shape[0], G, 32), axis=-1)",
        "den = np.linalg.norm((d + y).reshape(y.shape[0], G, 32), axis=-1)")]),
     ("group error statistic: ratio of whole-tensor norms instead of the mean of per-group ratios", "pipeline.py",
-     [("return float(np.mean(num[ok] / den[ok]))", "return float(np.linalg.norm(num[ok]) / np.linalg.norm(den[ok]))")]),
+     [("out[ok] = num[ok] / den[ok]", "out[ok] = np.linalg.norm(num[ok]) / np.linalg.norm(den[ok])")]),
     ("group error statistic: groups without norm counted in the mean", "pipeline.py",
-     [("return float(np.mean(num[ok] / den[ok]))", "return float(np.sum(num[ok] / den[ok]) / ok.size)")]),
+     [("return float(np.mean(r[r >= 0]))", "return float(np.sum(r[r >= 0]) / r.size)")]),
 ]
 
 

@@ -201,6 +201,10 @@ def test_group_error_statistic_on_hand_worked_groups():
     c, s = mxfp4.quantize(rows)
     got = pipeline.per_group_normalised_error(rows, c, s)
     assert abs(got - sum(ratios) / 4.0) <= 1e-7
+    # the same ratios group by group, the groups without norm marked -1
+    per = pipeline.per_group_normalised_errors(rows, c, s)
+    want = np.array([[ratios[0], -1.0, ratios[1]], [ratios[2], ratios[3], -1.0]])
+    assert per.shape == (2, 3) and np.max(np.abs(per - want)) <= 1e-7
 
 
 # ---------------------------------------------------------------- GEMM
