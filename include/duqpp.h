@@ -143,6 +143,21 @@ size_t duqpp_packed_rotation_bytes(int64_t n_rblocks);   /* host, pure; 0 for in
 int duqpp_pack_rotation(const float* R, int64_t n_rblocks, void* R_packed, void* stream);
 
 /*
+ * Per-group normalised quantisation error, the statistic of Fig. 1 (Sec. 4.1): for every token t and every group j
+ * of 32 channels, ||Q(y) - y||_2 / ||y||_2 with y the group after the block rotation of Eq. 4 and Q the quantiser of
+ * Eq. 2 -- rotated and quantised by the same device code as duqpp_rotate_quantize, so it is the error of the codes
+ * that call produces.  An analysis tool, not a step of the online path.
+ *   x_bf16  in   [T, K] bf16, row stride ldx elements (multiple of 8), 16-byte aligned; T <= 32 * 65535
+ *   R       in   [n_rblocks, 32, 32] fp32 with n_rblocks == K/32 or 1, or NULL: no rotation (y = x, the figure's
+ *                unrotated setting; n_rblocks is then ignored)
+ *   err     out  [T, K/32] fp32; -1 for a group whose 32 values are all zero (it has no ratio)
+ *   mean    out  nullable; one double in device memory, 8-byte aligned: the mean of err over the groups that have a
+ *                ratio (what the figure plots), summed in a fixed order; 0 when no group has one
+ */
+int duqpp_group_error(const void* x_bf16, int64_t T, int64_t K, int64_t ldx, const float* R, int64_t n_rblocks,
+                      float* err, double* mean, void* stream);
+
+/*
  * TEST ONLY: runs the quantiser stage of duqpp_rotate_quantize (group amax, E8M0 scale,
  * E2M1 rounding, packing -- Eq. 2) on caller-supplied fp32 values, so that every fp32 bit
  * pattern can be swept through the device code.

@@ -35,6 +35,7 @@ from .binding import (  # noqa: F401
     tiled_bytes,
     untile_operand,
     quantize_f32_dbg,
+    group_error,
     quantize_weights,
     rotate_quantize,
     rotq_gemm,

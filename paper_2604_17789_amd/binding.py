@@ -36,6 +36,7 @@ def _load():
     L.duqpp_mxfp4_gemm.argtypes = [u8p, u8p, u8p, u8p, i64, i64, i64, vp, ci, i64, vp, sz, vp]
     L.duqpp_rotq_gemm.argtypes = [vp, i64, fp, i64, u8p, u8p, i64, i64, i64, vp, ci, i64, vp, sz, vp]
     L.duqpp_quantize_f32_dbg.argtypes = [fp, i64, i64, i64, u8p, u8p, vp]
+    L.duqpp_group_error.argtypes = [vp, i64, i64, i64, fp, i64, fp, vp, vp]
     L.duqpp_gemm_workspace_bytes.argtypes = [i64, i64, i64, ci]
     L.duqpp_gemm_workspace_bytes.restype = sz
     L.duqpp_validate_rotate_quantize.argtypes = [vp, i64, i64, i64, fp, i64, u8p, u8p]
@@ -235,6 +236,28 @@ def quantize_f32_dbg(y):
     st = lib.duqpp_quantize_f32_dbg(y.data_ptr(), rows, K, y.stride(0), codes.data_ptr(), scales.data_ptr(), _stream())
     _check(st, "duqpp_quantize_f32_dbg")
     return codes, scales
+
+
+def group_error(x, R=None, return_mean=True):
+    """x bf16 [T, K], R fp32 [K/32 or 1, 32, 32] or None (no rotation) -> (err fp32 [T, K/32], mean): the per-group
+    normalised quantisation error of Sec. 4.1 (Fig. 1), -1 where a group is all zero, and its mean over the other
+    groups (a Python float; None with return_mean=False)."""
+    _dev(x, torch.bfloat16, "x")
+    T, K = x.shape
+    if x.stride(1) != 1:
+        raise ValueError("x must have unit stride along K")
+    nrb = 1
+    if R is not None:
+        _dev(R, torch.float32, "R")
+        if not R.is_contiguous() or R.dim() != 3 or tuple(R.shape[1:]) != (32, 32):
+            raise ValueError("R must be a contiguous [n, 32, 32] tensor")
+        nrb = R.shape[0]
+    err = torch.empty((T, K // 32), dtype=torch.float32, device=x.device)
+    mean = torch.empty(1, dtype=torch.float64, device=x.device) if return_mean else None
+    st = lib.duqpp_group_error(x.data_ptr(), T, K, x.stride(0), R.data_ptr() if R is not None else None, nrb,
+                               err.data_ptr(), mean.data_ptr() if mean is not None else None, _stream())
+    _check(st, "duqpp_group_error")
+    return err, (float(mean.item()) if mean is not None else None)
 
 
 # ---------------------------------------------------------------- tiled operand layout

@@ -260,6 +260,28 @@ int duqpp_rotq_gemm(const void* x_bf16, int64_t ldx, const float* R, int64_t n_r
     return launch_gemm_tiled(p, hs) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
 }
 
+int duqpp_group_error(const void* x_bf16, int64_t T, int64_t K, int64_t ldx, const float* R, int64_t n_rblocks,
+                      float* err, double* mean, void* stream) {
+    if (!x_bf16 || !err) return DUQPP_ERR_NULL;
+    int st = validate_rows_K(T, K, ldx, R ? n_rblocks : 1);
+    if (st != DUQPP_OK) return st;
+    if ((T + 31) / 32 > kGroupErrorMaxTiles) return DUQPP_ERR_TOO_LARGE;
+    if (!aligned_to(x_bf16, 16) || (ldx % 8) != 0) return DUQPP_ERR_ALIGN;
+    if ((R && !aligned_to(R, 4)) || !aligned_to(err, 4) || (mean && !aligned_to(mean, 8))) return DUQPP_ERR_ALIGN;
+    st = check_device();
+    if (st != DUQPP_OK) return st;
+    GroupErrorParams p{};
+    p.x = static_cast<const uint16_t*>(x_bf16);
+    p.ldx = ldx;
+    p.rows = (int)T;
+    p.G = (int)(K / 32);
+    p.R = R;
+    p.r_stride = (n_rblocks == 1) ? 0 : 32 * 32;
+    p.err = err;
+    p.mean = mean;
+    return launch_group_error(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DUQPP_OK : DUQPP_ERR_HIP;
+}
+
 int duqpp_quantize_f32_dbg(const float* y, int64_t rows, int64_t K, int64_t ldy, uint8_t* codes,
                            uint8_t* scales, void* stream) {
     if (!y || !codes || !scales) return DUQPP_ERR_NULL;

@@ -90,6 +90,23 @@ struct PackRotationParams {
 };
 hipError_t launch_pack_rotation(const PackRotationParams& p, hipStream_t stream);
 
+// ---- per-group normalised quantisation error (group_error.hip) --------------------------
+struct GroupErrorParams {
+    const uint16_t* x;   // bf16 [rows, K], stride ldx
+    int64_t ldx;
+    int rows;
+    int G;               // K / 32
+    const float* R;      // fp32 blocks, or null: no rotation
+    int r_stride;        // floats between consecutive blocks (0 when one block is shared)
+    float* err;          // [rows, G]
+    double* mean;        // nullable
+};
+struct GroupErrorMeanParams {
+    const float* err; int64_t n; double* mean;
+};
+constexpr int64_t kGroupErrorMaxTiles = 65535;   // token tiles along blockIdx.y
+hipError_t launch_group_error(const GroupErrorParams& p, hipStream_t stream);
+
 struct QuantDbgParams {
     const float* y; int64_t ldy; int rows; int G; uint8_t* codes; uint8_t* scales;
 };

@@ -78,10 +78,10 @@ __device__ __forceinline__ f32x16 rotate_tile(const RotOperand& op, const u32x4 
     return acc;
 }
 
-// Eq. 2 on one token's 32 values spread over lanes l and l^32 (16 each, layout of rotate_tile).
-// Returns the E8M0 byte; `out` receives this lane's 8 bytes of the group's 16 code bytes
-// (h = 0: bytes 0..7, h = 1: bytes 8..15).
-__device__ __forceinline__ uint32_t quantize_group(const f32x16& acc, uint2& out) {
+// Eq. 2 on one token's 32 values spread over lanes l and l^32 (16 each, layout of rotate_tile): the E8M0 byte of the
+// group, and this lane's own 16 codes -- acc[2 k], acc[2 k + 1] in the low and high nibble of byte k of p0 (k < 4),
+// acc[8 + 2 k], acc[9 + 2 k] likewise in p1.
+__device__ __forceinline__ uint32_t quantize_lane(const f32x16& acc, uint32_t& p0, uint32_t& p1) {
     float m = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(acc[i]));
@@ -90,7 +90,8 @@ __device__ __forceinline__ uint32_t quantize_group(const f32x16& acc, uint2& out
     uint32_t ef = __float_as_uint(m) >> 23;
     uint32_t byte = (ef > 2u ? ef : 2u) - 2u;
     float sc = __uint_as_float(byte << 23);
-    uint32_t p0 = 0, p1 = 0;
+    p0 = 0;
+    p1 = 0;
     p0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p0, acc[0], acc[1], sc, 0);
     p0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p0, acc[2], acc[3], sc, 1);
     p0 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p0, acc[4], acc[5], sc, 2);
@@ -99,6 +100,14 @@ __device__ __forceinline__ uint32_t quantize_group(const f32x16& acc, uint2& out
     p1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p1, acc[10], acc[11], sc, 1);
     p1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p1, acc[12], acc[13], sc, 2);
     p1 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p1, acc[14], acc[15], sc, 3);
+    return byte;
+}
+
+// The same with the codes in the order of the operand layouts.  Returns the E8M0 byte; `out` receives this lane's 8
+// bytes of the group's 16 code bytes (h = 0: bytes 0..7, h = 1: bytes 8..15).
+__device__ __forceinline__ uint32_t quantize_group(const f32x16& acc, uint2& out) {
+    uint32_t p0, p1;
+    const uint32_t byte = quantize_lane(acc, p0, p1);
     // p0 = code bytes {2h, 2h+1, 4+2h, 5+2h}, p1 = {8+2h, 9+2h, 12+2h, 13+2h}.
     // Swap p0 of the upper half-wave with p1 of the lower: h = 0 then holds both p0s, h = 1 both p1s.
     auto sw = __builtin_amdgcn_permlane32_swap(p0, p1, false, false);

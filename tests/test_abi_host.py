@@ -92,6 +92,13 @@ def test_entry_points_reject_bad_arguments_before_any_launch(lib):
     assert lib.duqpp_mxfp4_gemm(P, P, P, P, 8, 16, 64, P, 9, 16, None, 0, None) == DTYPE
     assert lib.duqpp_rotq_gemm(P, 64, P, 2, P, P, 8, 16, 64, P, 0, 16, None, 0, None) == WORKSPACE
     assert lib.duqpp_quantize_f32_dbg(None, 4, 64, 64, P, P, None) == NULL
+    assert lib.duqpp_group_error(None, 4, 64, 64, P, 2, P, None, None) == NULL
+    assert lib.duqpp_group_error(P, 4, 64, 64, P, 2, None, None, None) == NULL
+    assert lib.duqpp_group_error(P, 4, 64, 64, P, 3, P, None, None) == SHAPE      # n_rblocks not in {1, K/32}
+    assert lib.duqpp_group_error(P, 4, 48, 64, None, 0, P, None, None) == SHAPE   # K % 32, also without rotation
+    assert lib.duqpp_group_error(P, 32 * 65535 + 1, 64, 64, None, 0, P, None, None) == -8   # too many token tiles
+    assert lib.duqpp_group_error(P, 4, 64, 68, None, 0, P, None, None) == ALIGN   # row stride not a multiple of 8
+    assert lib.duqpp_group_error(P, 4, 64, 64, None, 0, P, P + 4, None) == ALIGN  # mean not 8-byte aligned
     assert lib.duqpp_fold_smoothing(P, 2, None, 64, P, P, None) == NULL
     assert lib.duqpp_fold_smoothing(P, 3, P, 64, P, P, None) == SHAPE      # n_rblocks not in {1, K/32}
     assert lib.duqpp_fold_smoothing(P, 2, P, 48, P, P, None) == SHAPE
