@@ -7,7 +7,8 @@ roundings to bf16 need not be the same rule, so two results may sit on neighbour
 -- except where a sum cancels to nearly nothing, where the order of the additions alone moves it by many of its own
 (tiny) bf16 steps: there the bar is absolute, 2e-4 of the outputs' root mean square (fp32 accumulation error of K
 terms against a result sqrt(K) times smaller than the sum of their magnitudes).
-Skipped where this torch build has no such call."""
+Skipped where this torch build has no such call, or where the library declines a shape (its heuristic has refused the
+64-token case on some boxes)."""
 import pytest
 
 import workloads as wl
@@ -24,7 +25,7 @@ def _library_product(torch, ac, asc, bc, bs):
         return F.scaled_mm(ac.view(fp4), bc.view(fp4).t(), asc.view(e8m0), recipe, bs.view(e8m0), recipe,
                            swizzle_a=noswz, swizzle_b=noswz, output_dtype=torch.bfloat16)
     except (AttributeError, RuntimeError, TypeError, ValueError) as exc:
-        pytest.skip(f"no block-scaled FP4 matmul in this torch build: {str(exc)[:120]}")
+        pytest.skip(f"the library's block-scaled FP4 matmul is not available for this case: {str(exc)[:120]}")
 
 
 def _bf16_steps_apart(torch, a, b):
